@@ -1,0 +1,256 @@
+/*
+ * CPU oracle for the 4-bit quantized GEMM / im2col-convolution path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  It shares no code, header, table or helper
+ * with the HIP sources; only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may call it.  Every pointer is a HOST pointer.
+ *
+ * What it follows (Trusov et al., "Fast Implementation of 4-bit Convolutional
+ * Neural Networks for Mobile Devices"):
+ *   - Sec. 2.2, Eq. (2), left-hand side: the quantized product is the sum over
+ *     the depth index of (code - zero_point) * (code - zero_point).  The
+ *     four-term expansion on the right-hand side of Eq. (2) / Eq. (3) is NOT
+ *     used here, so that tests can check it as an identity.
+ *   - Sec. 3.1: the result keeps zero point 0 and is stored as an integer
+ *     (here int32 instead of the paper's int16; accumulation is int64 and the
+ *     int32 range is asserted, the analogue of the depth bound of Eq. (5)).
+ *   - Sec. 3.1: convolution depth is D = k_h * k_w * c (im2col / "unrolling").
+ *   - Eq. (1) uses a floor; the integer re-quantization takes the same floor.
+ *
+ * Storage convention (not fixed by the paper, which keeps one code per byte in
+ * its temporary buffers): two codes per byte along the contiguous dimension,
+ * element 2j in bits 3:0 and element 2j+1 in bits 7:4 of byte j.
+ *
+ * Parity status: every function below is pinned by tests/test_oracle_*.py
+ * (hand-worked values, brute force, Eq. (2) identity, library routines).
+ */
+#include <stddef.h>
+#include <stdint.h>
+
+#define Q4O_OK 0
+#define Q4O_ERR_ARG (-1)
+#define Q4O_ERR_OVERFLOW (-5)
+
+/* code j of a packed row: low nibble holds the even index. */
+static inline int q4o_code(const uint8_t *row, long j)
+{
+    return (row[j >> 1] >> (4 * (int)(j & 1))) & 15;
+}
+
+int q4o_unpack(const uint8_t *packed, long n, uint8_t *codes)
+{
+    if (!packed || !codes || n < 0) return Q4O_ERR_ARG;
+    for (long j = 0; j < n; ++j) codes[j] = (uint8_t)q4o_code(packed, j);
+    return Q4O_OK;
+}
+
+/*
+ * codes: rows x cols, one code per byte (upper four bits ignored), leading
+ * dimension ld_src elements.  transpose == 0: dst has `rows` rows of
+ * ceil(cols/2) bytes; transpose != 0: dst has `cols` rows of ceil(rows/2)
+ * bytes and holds the transposed matrix.  An odd tail leaves the last high
+ * nibble zero.  ld_dst is in bytes.
+ */
+int q4o_pack(const uint8_t *codes, long rows, long cols, long ld_src,
+             int transpose, uint8_t *dst, long ld_dst)
+{
+    if (!codes || !dst || rows <= 0 || cols <= 0 || ld_src < cols) return Q4O_ERR_ARG;
+    long out_rows = transpose ? cols : rows;
+    long out_cols = transpose ? rows : cols;
+    if (ld_dst < (out_cols + 1) / 2) return Q4O_ERR_ARG;
+    for (long r = 0; r < out_rows; ++r) {
+        for (long b = 0; b < (out_cols + 1) / 2; ++b) dst[r * ld_dst + b] = 0;
+        for (long c = 0; c < out_cols; ++c) {
+            int v = transpose ? codes[c * ld_src + r] : codes[r * ld_src + c];
+            v &= 15;
+            dst[r * ld_dst + (c >> 1)] |= (uint8_t)(v << (4 * (int)(c & 1)));
+        }
+    }
+    return Q4O_OK;
+}
+
+/* sums[r] = sum over k of code (r, k) of a packed rows x k matrix. */
+int q4o_rowsum(const uint8_t *A, long rows, long k, long ld_bytes, int32_t *sums)
+{
+    if (!A || !sums || rows <= 0 || k <= 0 || ld_bytes < (k + 1) / 2) return Q4O_ERR_ARG;
+    for (long r = 0; r < rows; ++r) {
+        int64_t s = 0;
+        for (long j = 0; j < k; ++j) s += q4o_code(A + r * ld_bytes, j);
+        sums[r] = (int32_t)s;
+    }
+    return Q4O_OK;
+}
+
+/*
+ * C[m, n] = sum_k (A[m, k] - za) * (B[k, n] - zb)            Eq. (2), lhs.
+ * A: M rows of ceil(K/2) bytes (lda bytes apart).
+ * b_layout 0: B is K rows of ceil(N/2) bytes (pairs along n).
+ * b_layout 1: B is N rows of ceil(K/2) bytes (pairs along k).
+ * Accumulates in int64; a sum outside int32 is reported, never wrapped.
+ */
+int q4o_gemm(long M, long N, long K,
+             const uint8_t *A, long lda, int za,
+             const uint8_t *B, long ldb, int zb, int b_layout,
+             int32_t *C, long ldc)
+{
+    if (!A || !B || !C || M <= 0 || N <= 0 || K <= 0) return Q4O_ERR_ARG;
+    if (za < 0 || za > 15 || zb < 0 || zb > 15) return Q4O_ERR_ARG;
+    if (lda < (K + 1) / 2 || ldc < N) return Q4O_ERR_ARG;
+    if (b_layout == 0 ? ldb < (N + 1) / 2 : ldb < (K + 1) / 2) return Q4O_ERR_ARG;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (long m = 0; m < M; ++m) {
+        for (long n = 0; n < N; ++n) {
+            int64_t s = 0;
+            for (long k = 0; k < K; ++k) {
+                int a = q4o_code(A + m * lda, k);
+                int b = b_layout == 0 ? q4o_code(B + k * ldb, n)
+                                      : q4o_code(B + n * ldb, k);
+                s += (int64_t)(a - za) * (int64_t)(b - zb);
+            }
+            if (s > INT32_MAX || s < INT32_MIN) bad = 1;
+            C[m * ldc + n] = (int32_t)s;
+        }
+    }
+    return bad ? Q4O_ERR_OVERFLOW : Q4O_OK;
+}
+
+/*
+ * Quantized convolution, Sec. 3.1 with D = KH*KW*C:
+ *   y[n, oh, ow, oc] = sum_{kh, kw, c} (xv - zx) * (w[oc, kh, kw, c] - zw)
+ *   xv = x[n, oh*sh + kh - ph, ow*sw + kw - pw, c] inside the image, else zx
+ * x: NHWC codes as one flat packed array (code index ((n*H+h)*W+w)*C + c).
+ * w: OC rows of ceil(KH*KW*C/2) bytes, depth order (kh, kw, c), c fastest.
+ * y: int32, (N*OH*OW) x OC row-major.
+ */
+int q4o_conv2d(long N, long H, long W, long C, long KH, long KW,
+               long sh, long sw, long ph, long pw, long OC,
+               const uint8_t *x, int zx, const uint8_t *w, int zw, int32_t *y)
+{
+    if (!x || !w || !y) return Q4O_ERR_ARG;
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || KH <= 0 || KW <= 0 || OC <= 0) return Q4O_ERR_ARG;
+    if (sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return Q4O_ERR_ARG;
+    if (zx < 0 || zx > 15 || zw < 0 || zw > 15) return Q4O_ERR_ARG;
+    if (H + 2 * ph < KH || W + 2 * pw < KW) return Q4O_ERR_ARG;
+    long OH = (H + 2 * ph - KH) / sh + 1;
+    long OW = (W + 2 * pw - KW) / sw + 1;
+    long D = KH * KW * C;
+    long ldw = (D + 1) / 2;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (long p = 0; p < N * OH * OW; ++p) {
+        long n = p / (OH * OW);
+        long oh = (p / OW) % OH;
+        long ow = p % OW;
+        for (long oc = 0; oc < OC; ++oc) {
+            int64_t s = 0;
+            for (long kh = 0; kh < KH; ++kh)
+                for (long kw = 0; kw < KW; ++kw)
+                    for (long c = 0; c < C; ++c) {
+                        long ih = oh * sh + kh - ph;
+                        long iw = ow * sw + kw - pw;
+                        int xv = zx;
+                        if (ih >= 0 && ih < H && iw >= 0 && iw < W)
+                            xv = q4o_code(x, ((n * H + ih) * W + iw) * C + c);
+                        int wv = q4o_code(w + oc * ldw, (kh * KW + kw) * C + c);
+                        s += (int64_t)(xv - zx) * (int64_t)(wv - zw);
+                    }
+            if (s > INT32_MAX || s < INT32_MIN) bad = 1;
+            y[p * OC + oc] = (int32_t)s;
+        }
+    }
+    return bad ? Q4O_ERR_OVERFLOW : Q4O_OK;
+}
+
+/* floor(p / 2^shift) for any sign of p, written as a division so that it does
+ * not lean on how the compiler shifts negative numbers. */
+static inline int64_t q4o_floor_div_pow2(int64_t p, int shift)
+{
+    int64_t d = (int64_t)1 << shift;
+    int64_t q = p / d;
+    if (p % d != 0 && p < 0) q -= 1;
+    return q;
+}
+
+/*
+ * Integer re-quantization of a layer output back to 4-bit codes:
+ *   q = min(max(floor(acc * mult / 2^shift) + zo, qmin), qmax)
+ * (floor as in Eq. (1); the zero point is added after scaling, the clamp is
+ * last).  out holds `rows` rows of ceil(cols/2) bytes, ld_out bytes apart.
+ */
+int q4o_requant(const int32_t *acc, long rows, long cols, long ld_acc,
+                int32_t mult, int shift, int zo, int qmin, int qmax,
+                uint8_t *out, long ld_out)
+{
+    if (!acc || !out || rows <= 0 || cols <= 0 || ld_acc < cols) return Q4O_ERR_ARG;
+    if (mult < 0 || shift < 0 || shift > 62) return Q4O_ERR_ARG;
+    if (zo < 0 || zo > 15 || qmin < 0 || qmax > 15 || qmin > qmax) return Q4O_ERR_ARG;
+    if (ld_out < (cols + 1) / 2) return Q4O_ERR_ARG;
+    for (long r = 0; r < rows; ++r) {
+        for (long b = 0; b < (cols + 1) / 2; ++b) out[r * ld_out + b] = 0;
+        for (long c = 0; c < cols; ++c) {
+            int64_t p = (int64_t)acc[r * ld_acc + c] * (int64_t)mult;
+            int64_t q = q4o_floor_div_pow2(p, shift) + zo;
+            if (q < qmin) q = qmin;
+            if (q > qmax) q = qmax;
+            out[r * ld_out + (c >> 1)] |= (uint8_t)((int)q << (4 * (int)(c & 1)));
+        }
+    }
+    return Q4O_OK;
+}
+
+/* 2x2 max-pool, stride 2, on codes; NHWC flat packed in and out; odd H or W
+ * drop the last row / column (floor). */
+int q4o_maxpool2x2(const uint8_t *x, long N, long H, long W, long C, uint8_t *y)
+{
+    if (!x || !y || N <= 0 || H < 2 || W < 2 || C <= 0) return Q4O_ERR_ARG;
+    long OH = H / 2, OW = W / 2;
+    long total = N * OH * OW * C;
+    for (long b = 0; b < (total + 1) / 2; ++b) y[b] = 0;
+    for (long n = 0; n < N; ++n)
+        for (long i = 0; i < OH; ++i)
+            for (long j = 0; j < OW; ++j)
+                for (long c = 0; c < C; ++c) {
+                    int best = 0;
+                    for (long di = 0; di < 2; ++di)
+                        for (long dj = 0; dj < 2; ++dj) {
+                            int v = q4o_code(x, ((n * H + 2 * i + di) * W + 2 * j + dj) * C + c);
+                            if (v > best) best = v;
+                        }
+                    long o = ((n * OH + i) * OW + j) * C + c;
+                    y[o >> 1] |= (uint8_t)(best << (4 * (int)(o & 1)));
+                }
+    return Q4O_OK;
+}
+
+/*
+ * Largest depth D for which a sum of D products of two q-bit codes is
+ * guaranteed to fit the accumulator: floor(acc_max / (2^q - 1)^2), Sec. 3.1
+ * just before Eq. (5).  acc_max is 2^15-1 for the paper's int16, 2^16-1 for
+ * its unsigned variant, 2^31-1 for the int32 used here.
+ */
+long q4o_max_depth(int64_t acc_max, int q_bits)
+{
+    if (acc_max <= 0 || q_bits <= 0 || q_bits > 16) return Q4O_ERR_ARG;
+    int64_t top = ((int64_t)1 << q_bits) - 1;
+    return (long)(acc_max / (top * top));
+}
+
+/* Channel bound of Eq. (5) for a kh x kw kernel. */
+long q4o_max_channels(int64_t acc_max, int q_bits, long kh, long kw)
+{
+    if (kh <= 0 || kw <= 0) return Q4O_ERR_ARG;
+    long d = q4o_max_depth(acc_max, q_bits);
+    return d < 0 ? d : d / (kh * kw);
+}
+
+/* Number of OpenMP threads the loops above will use (1 without OpenMP). */
+#ifdef _OPENMP
+#include <omp.h>
+int q4o_threads(void) { return omp_get_max_threads(); }
+void q4o_set_threads(int n) { if (n > 0) omp_set_num_threads(n); }
+#else
+int q4o_threads(void) { return 1; }
+void q4o_set_threads(int n) { (void)n; }
+#endif

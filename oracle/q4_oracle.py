@@ -1,0 +1,216 @@
+"""CPU oracle for the 4-bit quantized GEMM / convolution path (Python side).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the
+benchmark's cpu_baseline leg, never by the product package.  It shares no code
+with the HIP library.
+
+Two independent forms live here:
+
+* thin ctypes wrappers over ``q4_oracle.c`` (plain loops, int64 accumulation,
+  the left-hand side of Eq. (2) of the paper written out), and
+* a NumPy form (``gemm_f64``) that subtracts the zero points and calls the
+  BLAS float64 matrix product.  Every partial sum is an integer below 2**53,
+  so the float64 result is exact; it is the only form fast enough to check a
+  full 8192 x 8192 x 8192 product element by element.  It is pinned against
+  the plain loops in tests/test_oracle_gemm.py.
+
+All arrays are host NumPy arrays.  Packed storage: code 2j in bits 3:0 and code
+2j+1 in bits 7:4 of byte j along the contiguous dimension.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "q4_oracle.c")
+_LIB = os.path.join(_HERE, "libq4oracle.so")
+
+OK = 0
+ERR_ARG = -1
+ERR_OVERFLOW = -5
+
+B_KN = 0  # B stored as K rows of ceil(N/2) bytes
+B_NK = 1  # B stored as N rows of ceil(K/2) bytes
+
+
+def build(force: bool = False) -> str:
+    """Compile q4_oracle.c with gcc (-O2 -fopenmp) into libq4oracle.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+             "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        L, I, P = ctypes.c_long, ctypes.c_int, ctypes.c_void_p
+        lib.q4o_unpack.argtypes = [P, L, P]
+        lib.q4o_pack.argtypes = [P, L, L, L, I, P, L]
+        lib.q4o_rowsum.argtypes = [P, L, L, L, P]
+        lib.q4o_gemm.argtypes = [L, L, L, P, L, I, P, L, I, I, P, L]
+        lib.q4o_conv2d.argtypes = [L] * 11 + [P, I, P, I, P]
+        lib.q4o_requant.argtypes = [P, L, L, L, ctypes.c_int32, I, I, I, I, P, L]
+        lib.q4o_maxpool2x2.argtypes = [P, L, L, L, L, P]
+        lib.q4o_max_depth.argtypes = [ctypes.c_int64, I]
+        lib.q4o_max_depth.restype = L
+        lib.q4o_max_channels.argtypes = [ctypes.c_int64, I, L, L]
+        lib.q4o_max_channels.restype = L
+        lib.q4o_threads.restype = I
+        lib.q4o_set_threads.argtypes = [I]
+        lib.q4o_set_threads.restype = None
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _u8(a) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    return a
+
+
+def _check(rc: int, what: str):
+    if rc == ERR_OVERFLOW:
+        raise OverflowError(f"{what}: result does not fit int32")
+    if rc != OK:
+        raise ValueError(f"{what}: bad argument (rc={rc})")
+
+
+def threads() -> int:
+    return int(_load().q4o_threads())
+
+
+def set_threads(n: int) -> None:
+    _load().q4o_set_threads(int(n))
+
+
+def unpack(packed, n: int) -> np.ndarray:
+    """First n codes of a packed byte string."""
+    packed = _u8(packed).reshape(-1)
+    assert packed.size * 2 >= n
+    out = np.empty(n, dtype=np.uint8)
+    _check(_load().q4o_unpack(_ptr(packed), n, _ptr(out)), "unpack")
+    return out
+
+
+def unpack_rows(packed, rows: int, cols: int) -> np.ndarray:
+    """rows x ceil(cols/2) packed bytes -> rows x cols codes."""
+    packed = _u8(packed).reshape(rows, -1)
+    return np.stack([unpack(packed[r], cols) for r in range(rows)]) if rows else np.empty((0, cols), np.uint8)
+
+
+def pack(codes, transpose: bool = False) -> np.ndarray:
+    """rows x cols codes (one per byte) -> packed rows (optionally of the transpose)."""
+    codes = _u8(codes)
+    assert codes.ndim == 2
+    rows, cols = codes.shape
+    orows, ocols = (cols, rows) if transpose else (rows, cols)
+    out = np.empty((orows, (ocols + 1) // 2), dtype=np.uint8)
+    _check(_load().q4o_pack(_ptr(codes), rows, cols, cols, int(transpose), _ptr(out), out.shape[1]), "pack")
+    return out
+
+
+def rowsum(A, k: int) -> np.ndarray:
+    A = _u8(A)
+    assert A.ndim == 2
+    out = np.empty(A.shape[0], dtype=np.int32)
+    _check(_load().q4o_rowsum(_ptr(A), A.shape[0], k, A.shape[1], _ptr(out)), "rowsum")
+    return out
+
+
+def gemm(A, za: int, B, zb: int, M: int, N: int, K: int, b_layout: int = B_KN) -> np.ndarray:
+    """Plain-loop product of packed A (M x ceil(K/2)) and packed B; int32 M x N."""
+    A = _u8(A)
+    B = _u8(B)
+    assert A.ndim == 2 and B.ndim == 2 and A.shape[0] >= M
+    C = np.empty((M, N), dtype=np.int32)
+    rc = _load().q4o_gemm(M, N, K, _ptr(A), A.shape[1], za, _ptr(B), B.shape[1], zb, b_layout, _ptr(C), N)
+    _check(rc, "gemm")
+    return C
+
+
+def gemm_rows(A, za: int, B, zb: int, rows, N: int, K: int, b_layout: int = B_KN) -> np.ndarray:
+    """Plain-loop product for a chosen list of rows of A only (len(rows) x N)."""
+    A = _u8(A)
+    sel = np.ascontiguousarray(A[np.asarray(rows, dtype=np.int64)])
+    return gemm(sel, za, B, zb, len(rows), N, K, b_layout)
+
+
+def gemm_f64(A, za: int, B, zb: int, M: int, N: int, K: int, b_layout: int = B_KN) -> np.ndarray:
+    """Same product through the BLAS float64 matmul of the offset integers (exact)."""
+    Ac = _np_unpack_rows(_u8(A)[:M], K).astype(np.float64) - float(za)
+    if b_layout == B_KN:
+        Bc = _np_unpack_rows(_u8(B)[:K], N).astype(np.float64) - float(zb)      # K x N
+    else:
+        Bc = (_np_unpack_rows(_u8(B)[:N], K).astype(np.float64) - float(zb)).T   # K x N
+    C = Ac @ Bc
+    assert np.abs(C).max() < 2.0 ** 31
+    return C.astype(np.int64).astype(np.int32)
+
+
+def _np_unpack_rows(packed: np.ndarray, cols: int) -> np.ndarray:
+    """NumPy form of the nibble order, independent of the C loops."""
+    rows = packed.shape[0]
+    out = np.empty((rows, packed.shape[1] * 2), dtype=np.uint8)
+    out[:, 0::2] = packed & 15
+    out[:, 1::2] = packed >> 4
+    return out[:, :cols]
+
+
+def conv2d(x, zx: int, w, zw: int, N: int, H: int, W: int, C: int, KH: int, KW: int,
+           stride=(1, 1), pad=(0, 0), OC: int = 1) -> np.ndarray:
+    """x: flat packed NHWC codes; w: OC x ceil(KH*KW*C/2) bytes; -> (N*OH*OW) x OC int32."""
+    x = _u8(x).reshape(-1)
+    w = _u8(w)
+    D = KH * KW * C
+    assert x.size * 2 >= N * H * W * C
+    assert w.shape == (OC, (D + 1) // 2)
+    OH = (H + 2 * pad[0] - KH) // stride[0] + 1
+    OW = (W + 2 * pad[1] - KW) // stride[1] + 1
+    y = np.empty((N * OH * OW, OC), dtype=np.int32)
+    rc = _load().q4o_conv2d(N, H, W, C, KH, KW, stride[0], stride[1], pad[0], pad[1], OC,
+                            _ptr(x), zx, _ptr(w), zw, _ptr(y))
+    _check(rc, "conv2d")
+    return y
+
+
+def requant(acc, mult: int, shift: int, zo: int, qmin: int = 0, qmax: int = 15) -> np.ndarray:
+    """int32 rows x cols -> packed codes rows x ceil(cols/2)."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    assert acc.ndim == 2
+    rows, cols = acc.shape
+    out = np.empty((rows, (cols + 1) // 2), dtype=np.uint8)
+    rc = _load().q4o_requant(_ptr(acc), rows, cols, cols, mult, shift, zo, qmin, qmax, _ptr(out), out.shape[1])
+    _check(rc, "requant")
+    return out
+
+
+def maxpool2x2(x, N: int, H: int, W: int, C: int) -> np.ndarray:
+    """Flat packed NHWC codes -> flat packed N x H//2 x W//2 x C codes."""
+    x = _u8(x).reshape(-1)
+    assert x.size * 2 >= N * H * W * C
+    total = N * (H // 2) * (W // 2) * C
+    y = np.empty((total + 1) // 2, dtype=np.uint8)
+    _check(_load().q4o_maxpool2x2(_ptr(x), N, H, W, C, _ptr(y)), "maxpool2x2")
+    return y
+
+
+def max_depth(acc_max: int, q_bits: int) -> int:
+    return int(_load().q4o_max_depth(acc_max, q_bits))
+
+
+def max_channels(acc_max: int, q_bits: int, kh: int, kw: int) -> int:
+    return int(_load().q4o_max_channels(acc_max, q_bits, kh, kw))

@@ -1,0 +1,124 @@
+"""Pins for the oracle convolution and re-quantization."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import q4_oracle as o
+
+
+def _flat(x):
+    return o.pack(np.ascontiguousarray(x).reshape(1, -1)).reshape(-1)
+
+
+def _wpack(w):
+    return o.pack(np.ascontiguousarray(w).reshape(w.shape[0], -1))
+
+
+def test_handworked_3x3(golden):
+    g = golden("handworked.txt")
+    x = np.array(g["conv_x"], dtype=np.uint8).reshape(1, 3, 3, 1)
+    w = np.array(g["conv_w"], dtype=np.uint8).reshape(1, 3, 3, 1)
+    y = o.conv2d(_flat(x), g["conv_zx"], _wpack(w), g["conv_zw"], 1, 3, 3, 1, 3, 3, (1, 1), (1, 1), 1)
+    assert y.reshape(3, 3).tolist() == g["conv_y"]
+
+
+CASES = [
+    # N, H, W, C, KH, KW, stride, pad, OC
+    (1, 5, 5, 1, 3, 3, (1, 1), (1, 1), 2),
+    (2, 6, 7, 3, 3, 3, (1, 1), (0, 0), 4),
+    (1, 9, 8, 2, 5, 5, (1, 1), (0, 0), 3),
+    (2, 9, 11, 4, 3, 3, (2, 2), (0, 0), 5),
+    (1, 8, 10, 5, 3, 2, (2, 1), (1, 0), 3),
+    (1, 7, 7, 8, 1, 1, (1, 1), (0, 0), 6),
+    (1, 6, 6, 32, 3, 3, (1, 1), (1, 1), 8),
+    (1, 4, 9, 1, 3, 3, (1, 1), (2, 3), 2),
+]
+
+
+@pytest.mark.parametrize("N,H,W,C,KH,KW,stride,pad,OC", CASES)
+def test_conv_vs_torch_float64(N, H, W, C, KH, KW, stride, pad, OC):
+    """torch's conv2d on float64 tensors of the offset integers is exact (all sums < 2^53);
+    it pins padding, stride, depth order and the NHWC layouts."""
+    rng = np.random.default_rng(H * 100 + W * 10 + C)
+    zx, zw = (int(v) for v in rng.integers(0, 16, size=2))
+    x = rng.integers(0, 16, size=(N, H, W, C), dtype=np.uint8)
+    w = rng.integers(0, 16, size=(OC, KH, KW, C), dtype=np.uint8)
+    y = o.conv2d(_flat(x), zx, _wpack(w), zw, N, H, W, C, KH, KW, stride, pad, OC)
+    xt = torch.from_numpy(x.astype(np.float64) - zx).permute(0, 3, 1, 2)
+    wt = torch.from_numpy(w.astype(np.float64) - zw).permute(0, 3, 1, 2)
+    ref = torch.nn.functional.conv2d(xt, wt, stride=stride, padding=pad)      # zero padding == pad code zx
+    ref = ref.permute(0, 2, 3, 1).reshape(-1, OC).numpy()
+    assert y.shape == ref.shape
+    assert np.array_equal(y, ref.astype(np.int64))
+
+
+def test_conv_equals_explicit_unrolling_then_gemm():
+    """Sec. 3.1: convolution = GEMM on the unrolled input with depth D = kh*kw*c."""
+    rng = np.random.default_rng(77)
+    N, H, W, C, OC, zx, zw = 2, 6, 5, 3, 4, 9, 4
+    x = rng.integers(0, 16, size=(N, H, W, C), dtype=np.uint8)
+    w = rng.integers(0, 16, size=(OC, 3, 3, C), dtype=np.uint8)
+    xp = np.full((N, H + 2, W + 2, C), zx, dtype=np.uint8)
+    xp[:, 1:-1, 1:-1, :] = x
+    rows = [xp[n, oh:oh + 3, ow:ow + 3, :].reshape(-1) for n in range(N) for oh in range(H) for ow in range(W)]
+    a = np.stack(rows)                                   # (N*H*W) x 27
+    got = o.conv2d(_flat(x), zx, _wpack(w), zw, N, H, W, C, 3, 3, (1, 1), (1, 1), OC)
+    want = o.gemm(o.pack(a), zx, _wpack(w), zw, N * H * W, OC, 27, o.B_NK)
+    assert np.array_equal(got, want)
+
+
+def test_paper_cnn_shapes_and_depths(golden):
+    """Table 2 / Sec. 4.2: 25x33 input, valid convs -> 1x3 map; 8264 conv and 10892 total parameters;
+    every depth kh*kw*c stays within the int16 bound of Sec. 3.1."""
+    g = golden("paper_constants.txt")
+    H, W = g["cnn_input"]
+    c, conv_params, depths = 1, 0, []
+    rng = np.random.default_rng(1)
+    for filters, k, s in g["cnn_layers"]:
+        x = rng.integers(0, 16, size=(1, H, W, c), dtype=np.uint8)
+        w = rng.integers(0, 16, size=(filters, k, k, c), dtype=np.uint8)
+        y = o.conv2d(_flat(x), 3, _wpack(w), 5, 1, H, W, c, k, k, (s, s), (0, 0), filters)
+        OH, OW = (H - k) // s + 1, (W - k) // s + 1
+        assert y.shape == (OH * OW, filters)
+        depths.append(k * k * c)
+        conv_params += filters * k * k * c
+        H, W, c = OH, OW, filters
+    assert (H, W) == (1, 3)
+    assert conv_params == g["cnn_conv_params"]
+    assert conv_params + g["cnn_fc_neurons"] * (c * H * W + 1) == g["cnn_total_params"]
+    assert depths == [25, 72, 72, 72, 144, 144]
+    assert max(depths) <= o.max_depth(2 ** 15 - 1, 4) == g["depth_bound_int16"]
+    assert g["big_kernel_rows"] * g["big_kernel_cols"] * 2 * 2 == g["big_kernel_muladds"]
+
+
+def test_requant_handworked(golden):
+    g = golden("handworked.txt")
+    for mult, acc, want in g["requant_a"] + g["requant_b"]:
+        out = o.requant(np.array([[acc]], dtype=np.int32), mult, 20, 8)
+        assert o.unpack(out, 1).tolist() == [want], (mult, acc)
+
+
+def test_requant_vs_python_bigint():
+    rng = np.random.default_rng(3)
+    for _ in range(40):
+        rows, cols = int(rng.integers(1, 5)), int(rng.integers(1, 12))
+        mult = int(rng.integers(0, 2 ** 31))
+        shift = int(rng.integers(0, 63))
+        zo = int(rng.integers(0, 16))
+        qmin = int(rng.integers(0, 16))
+        qmax = int(rng.integers(qmin, 16))
+        acc = rng.integers(-2 ** 31, 2 ** 31, size=(rows, cols), dtype=np.int64).astype(np.int32)
+        acc.flat[0] = [-2 ** 31, 2 ** 31 - 1, 0, -1][_ % 4]
+        got = o.unpack_rows(o.requant(acc, mult, shift, zo, qmin, qmax), rows, cols)
+        want = [[min(max((int(v) * mult) // (1 << shift) + zo, qmin), qmax) for v in r] for r in acc.tolist()]
+        assert got.tolist() == want
+
+
+def test_requant_monotone_and_in_range():
+    acc = np.arange(-5000, 5000, dtype=np.int32).reshape(1, -1)
+    q = o.unpack_rows(o.requant(acc, 30000, 18, 8), 1, acc.size)[0].astype(int)
+    assert np.all(np.diff(q) >= 0) and q.min() == 0 and q.max() == 15
+    # ReLU before re-quantization == lower clamp at the zero point (floor is monotone, floor(0) = 0)
+    relu = o.unpack_rows(o.requant(np.maximum(acc, 0), 30000, 18, 8), 1, acc.size)
+    clamp = o.unpack_rows(o.requant(acc, 30000, 18, 8, qmin=8), 1, acc.size)
+    assert np.array_equal(relu, clamp)
