@@ -1,0 +1,184 @@
+/*
+ * libq4 -- exact 4-bit quantized matrix multiplication and im2col convolution
+ * for AMD MI355X (gfx950).  C ABI.
+ *
+ * The operations are those of Trusov, Limonova, Slugin, Nikolaev, Arlazarov,
+ * "Fast Implementation of 4-bit Convolutional Neural Networks for Mobile
+ * Devices" (arXiv 2009.06488): unsigned 4-bit codes with one zero point per
+ * tensor, multiplied with widening into an integer accumulator (Sec. 2.2),
+ * which is what GEMM-based convolution of a 4-bit network reduces to
+ * (Sec. 1, Sec. 3.1).  The accumulator here is int32 (the paper uses 16 bits
+ * and therefore limits the depth, Eq. (5)); results are exact.
+ *
+ * Conventions common to every call
+ *   - Returns Q4_OK (0) or a negative Q4_ERR_* code; never throws.
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  Descriptor
+ *     structs (q4_conv_desc) are HOST pointers, read during the call only.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it; no call synchronises, allocates or frees.
+ *   - Arguments are validated on the host before the first HIP call, so every
+ *     error except Q4_ERR_HIP is returned without touching the GPU.
+ *   - Source and destination buffers must not overlap.
+ *   - Packed storage: two codes per byte along the contiguous dimension,
+ *     element 2j in bits 3:0 and element 2j+1 in bits 7:4 of byte j.  A row of
+ *     odd length ends in a byte whose high nibble is ignored on input and
+ *     written as zero on output.
+ *   - Orientation: C = (A - za) (B - zb) with activations A on the left
+ *     (M x K, one row per im2col patch) and weights B on the right (K x N).
+ *     The paper writes R = W X with the weights on the left; C is R transposed,
+ *     za is its z_x, zb its z_w, K its depth D.
+ */
+#ifndef Q4_H
+#define Q4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    Q4_OK = 0,
+    Q4_ERR_NULL = -1,      /* a required pointer is NULL */
+    Q4_ERR_SHAPE = -2,     /* a dimension is <= 0 or a leading dimension is too small */
+    Q4_ERR_RANGE = -3,     /* zero point / clamp outside 0..15, mult < 0, shift outside 0..62 */
+    Q4_ERR_ALIGN = -4,     /* int32 pointer not 4-byte aligned */
+    Q4_ERR_OVERFLOW = -5,  /* depth * 225 would not fit int32 (depth > 9544371) */
+    Q4_ERR_WORKSPACE = -6, /* workspace NULL or smaller than the matching *_workspace_bytes */
+    Q4_ERR_LAYOUT = -7,    /* unknown b_layout */
+    Q4_ERR_HIP = -8        /* a kernel launch failed (hipGetLastError holds the cause) */
+};
+
+/* Library version: major * 10000 + minor * 100 + patch.  Host only. */
+int q4_version(void);
+
+/* Static string for an error code.  Host only. */
+const char *q4_strerror(int code);
+
+/* Largest depth K accepted by q4_gemm / q4_conv2d_im2col: floor((2^31 - 1) / 15^2),
+ * the int32 form of the depth bound the paper derives for 16-bit accumulators
+ * (Sec. 3.1, the sentence before Eq. (5)).  Host only. */
+int q4_max_depth(void);
+
+/*
+ * q4_pack -- store codes two per byte (the counterpart of packing operands into
+ * the paper's temporary buffers before the multiplication, Sec. 2.3; the paper
+ * keeps one code per byte, the 2-per-byte order is the convention above).
+ *   src : rows x cols codes, one per byte, row-major, ld_src elements between rows.
+ *         Only the low four bits of each byte are used.
+ *   transpose == 0 : dst has `rows` rows of ceil(cols/2) bytes.
+ *   transpose != 0 : dst has `cols` rows of ceil(rows/2) bytes and holds the
+ *         transposed matrix (turns a K x N weight matrix into the N x K form
+ *         q4_gemm multiplies fastest).
+ *   ld_dst_bytes : bytes between dst rows (>= the row length above).
+ */
+int q4_pack(const uint8_t *src, int rows, int cols, int ld_src, int transpose,
+            uint8_t *dst, int ld_dst_bytes, void *stream);
+
+/*
+ * q4_rowsum -- sums[r] = sum_k code(r, k) of a packed rows x k matrix: the
+ * depth sums that multiply the zero points in the second and third terms of Eq. (2).
+ * For weights in N x K form this is the per-output-channel sum the paper
+ * stores with the layer (Sec. 3.2).
+ */
+int q4_rowsum(const uint8_t *A, int rows, int k, int ld_bytes, int32_t *sums, void *stream);
+
+/*
+ * q4_repack_kn_to_nk -- transpose a packed K x N matrix (K rows of ceil(N/2)
+ * bytes) into packed N x K form (N rows of ceil(K/2) bytes).  Weights do not
+ * change between inferences, so this is done once per layer (Sec. 2.2).
+ */
+int q4_repack_kn_to_nk(const uint8_t *B_kn, int K, int N, int ldb_bytes,
+                       uint8_t *B_nk, int ld_out_bytes, void *stream);
+
+enum {
+    Q4_B_KN = 0, /* B is K rows of ceil(N/2) bytes: codes paired along n */
+    Q4_B_NK = 1  /* B is N rows of ceil(K/2) bytes: codes paired along k */
+};
+
+/* Bytes of device workspace q4_gemm needs for this shape and layout (row and
+ * column sums; for Q4_B_KN also the re-packed copy of B).  Host only.
+ * Returns 0 for invalid arguments. */
+size_t q4_gemm_workspace_bytes(int M, int N, int K, int b_layout);
+
+/*
+ * q4_gemm -- C[m*ldc + n] = sum_{k<K} (A[m,k] - za) * (B[k,n] - zb), exact int32:
+ * the quantized product of Eq. (2) / Eq. (3) with z_r = 0 (Sec. 3.1).
+ *   A : M rows of ceil(K/2) bytes, lda_bytes apart.   0 <= za <= 15.
+ *   B : per b_layout, rows ldb_bytes apart.           0 <= zb <= 15.
+ *   C : M x N int32, row-major, ldc elements between rows (>= N).
+ *   workspace : >= q4_gemm_workspace_bytes(M, N, K, b_layout) bytes, 16-byte aligned.
+ * Computed as in the right-hand side of Eq. (2): raw code products on the
+ * matrix cores, then the row-sum, column-sum and constant terms in the epilogue.
+ * Any M, N, K >= 1 and any alignment of A and B are accepted.
+ */
+int q4_gemm(int M, int N, int K,
+            const uint8_t *A, int lda_bytes, int za,
+            const uint8_t *B, int ldb_bytes, int zb, int b_layout,
+            int32_t *C, int ldc,
+            void *workspace, size_t workspace_bytes, void *stream);
+
+typedef struct {
+    int N, H, W, C;         /* input: batch, height, width, channels (NHWC) */
+    int KH, KW;             /* kernel size */
+    int stride_h, stride_w; /* >= 1 */
+    int pad_h, pad_w;       /* >= 0, same on both sides */
+    int OC;                 /* output channels */
+} q4_conv_desc;
+
+/* Bytes of device workspace q4_conv2d_im2col needs.  Host only.  0 if invalid. */
+size_t q4_conv2d_workspace_bytes(const q4_conv_desc *desc);
+
+/*
+ * q4_conv2d_im2col -- quantized convolution as a GEMM over unrolled patches
+ * (Sec. 1, Sec. 3.1 with depth D = KH*KW*C); the patch matrix is never
+ * materialised, it is gathered while the tiles are loaded.
+ *   x : NHWC codes as one flat packed array (code index ((n*H+h)*W+w)*C + c).
+ *   w : OC rows of ceil(KH*KW*C/2) bytes (tightly packed rows), depth order
+ *       (kh, kw, c) with c fastest -- the "unrolled" weight matrix of Sec. 3.2.
+ *   w_colsum : optional OC precomputed sums of each weight row (what
+ *       q4_rowsum(w, OC, KH*KW*C, ...) returns), or NULL to compute them here.
+ *   y : int32, (N*OH*OW) x OC row-major (NHWC),
+ *       OH = (H + 2*pad_h - KH) / stride_h + 1 (floor), likewise OW.
+ *   y[n,oh,ow,oc] = sum (xv - zx) * (w[oc,kh,kw,c] - zw), where xv is the input
+ *   code at (oh*stride_h + kh - pad_h, ow*stride_w + kw - pad_w) and reads as
+ *   zx outside the image, so padding contributes exactly zero.
+ */
+int q4_conv2d_im2col(const q4_conv_desc *desc, const uint8_t *x, int zx,
+                     const uint8_t *w, int zw, const int32_t *w_colsum,
+                     int32_t *y, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * q4_requant -- bring an int32 layer output back to 4-bit codes for the next
+ * quantized layer (the Q -> Q transition of Sec. 3.2), in integer form:
+ *   out(r, c) = min(max(floor(acc[r*ld_acc + c] * mult / 2^shift) + zo, qmin), qmax)
+ * with the floor of Eq. (1) (toward minus infinity, also for negative acc),
+ * packed two per byte along c.  A ReLU before re-quantization is qmin = zo.
+ *   0 <= mult < 2^31, 0 <= shift <= 62, 0 <= zo <= 15, 0 <= qmin <= qmax <= 15.
+ */
+int q4_requant(const int32_t *acc, long rows, int cols, long ld_acc,
+               int32_t mult, int shift, int zo, int qmin, int qmax,
+               uint8_t *out, long ld_out_bytes, void *stream);
+
+/*
+ * q4_maxpool2x2 -- 2x2 max-pool with stride 2 on packed NHWC codes (valid on
+ * codes because q4_requant is monotone).  C must be even; odd H or W drop the
+ * last row / column.  y is N x (H/2) x (W/2) x C, packed.
+ * Not part of the paper's network, which downsamples with strided convolutions.
+ */
+int q4_maxpool2x2(const uint8_t *x, int N, int H, int W, int C, uint8_t *y, void *stream);
+
+/*
+ * q4_debug_force_tile -- testing hook: force the output-tile size q4_gemm and
+ * q4_conv2d_im2col use (0 = 256x256, 1 = 128x128, 2 = 64x64; anything else
+ * restores selection by shape).  The result never depends on the tile.  The
+ * environment variable Q4_TILE=0|1|2 does the same when no override is set.
+ * Host only; not thread-safe.
+ */
+void q4_debug_force_tile(int tile);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* Q4_H */

@@ -1,0 +1,243 @@
+// C ABI of libq4: argument validation on the host, workspace carving, kernel launches.
+// Nothing here touches the GPU before every argument has been checked.
+#include <limits.h>
+#include <stdlib.h>
+
+#include "../../include/q4.h"
+#include "q4_kernels.h"
+
+namespace {
+
+constexpr int kMaxDepth = 9544371;  // floor((2^31 - 1) / 225)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool code_ok(int z) { return z >= 0 && z <= 15; }
+inline int rc_of(hipError_t e) { return e == hipSuccess ? Q4_OK : Q4_ERR_HIP; }
+
+int g_force_tile = -1;
+
+int tile_override()
+{
+    if (g_force_tile >= 0) return g_force_tile;
+    const char *e = getenv("Q4_TILE");
+    if (e && e[0] >= '0' && e[0] <= '2' && e[1] == 0) return e[0] - '0';
+    return -1;
+}
+
+// Row pitch of the N x K copy of B that q4_gemm makes for Q4_B_KN input.
+inline size_t nk_pitch(int K) { return align_up(static_cast<size_t>((K + 1) / 2), 16); }
+
+bool conv_out_dims(const q4_conv_desc *d, int *OH, int *OW)
+{
+    if (d->N <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->KH <= 0 || d->KW <= 0 || d->OC <= 0) return false;
+    if (d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0) return false;
+    const long eh = static_cast<long>(d->H) + 2L * d->pad_h - d->KH;
+    const long ew = static_cast<long>(d->W) + 2L * d->pad_w - d->KW;
+    if (eh < 0 || ew < 0) return false;
+    const long oh = eh / d->stride_h + 1, ow = ew / d->stride_w + 1;
+    if (static_cast<long>(d->N) * oh * ow > INT_MAX) return false;
+    if (static_cast<long>(d->KH) * d->KW * d->C > INT_MAX) return false;
+    *OH = static_cast<int>(oh);
+    *OW = static_cast<int>(ow);
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+int q4_version(void) { return 100; }
+
+const char *q4_strerror(int code)
+{
+    switch (code) {
+    case Q4_OK: return "ok";
+    case Q4_ERR_NULL: return "a required pointer is NULL";
+    case Q4_ERR_SHAPE: return "a dimension is not positive or a leading dimension is too small";
+    case Q4_ERR_RANGE: return "zero point, clamp, multiplier or shift out of range";
+    case Q4_ERR_ALIGN: return "pointer not sufficiently aligned";
+    case Q4_ERR_OVERFLOW: return "depth too large for an exact int32 result";
+    case Q4_ERR_WORKSPACE: return "workspace missing or too small";
+    case Q4_ERR_LAYOUT: return "unknown layout of B";
+    case Q4_ERR_HIP: return "kernel launch failed";
+    default: return "unknown error code";
+    }
+}
+
+int q4_max_depth(void) { return kMaxDepth; }
+
+void q4_debug_force_tile(int tile) { g_force_tile = (tile >= 0 && tile <= 2) ? tile : -1; }
+
+int q4_pack(const uint8_t *src, int rows, int cols, int ld_src, int transpose,
+            uint8_t *dst, int ld_dst_bytes, void *stream)
+{
+    if (!src || !dst) return Q4_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || ld_src < cols) return Q4_ERR_SHAPE;
+    const int out_cols = transpose ? rows : cols;
+    if (ld_dst_bytes < (out_cols + 1) / 2) return Q4_ERR_SHAPE;
+    return rc_of(q4::launch_pack(src, rows, cols, ld_src, transpose ? 1 : 0, dst, ld_dst_bytes,
+                                 static_cast<hipStream_t>(stream)));
+}
+
+int q4_rowsum(const uint8_t *A, int rows, int k, int ld_bytes, int32_t *sums, void *stream)
+{
+    if (!A || !sums) return Q4_ERR_NULL;
+    if (rows <= 0 || k <= 0 || ld_bytes < (k + 1) / 2) return Q4_ERR_SHAPE;
+    if (k > kMaxDepth) return Q4_ERR_OVERFLOW;
+    if (reinterpret_cast<uintptr_t>(sums) % 4) return Q4_ERR_ALIGN;
+    return rc_of(q4::launch_rowsum(A, rows, k, ld_bytes, sums, static_cast<hipStream_t>(stream)));
+}
+
+int q4_repack_kn_to_nk(const uint8_t *B_kn, int K, int N, int ldb_bytes,
+                       uint8_t *B_nk, int ld_out_bytes, void *stream)
+{
+    if (!B_kn || !B_nk) return Q4_ERR_NULL;
+    if (K <= 0 || N <= 0 || ldb_bytes < (N + 1) / 2 || ld_out_bytes < (K + 1) / 2) return Q4_ERR_SHAPE;
+    return rc_of(q4::launch_repack_kn_to_nk(B_kn, K, N, ldb_bytes, B_nk, ld_out_bytes,
+                                            static_cast<hipStream_t>(stream)));
+}
+
+size_t q4_gemm_workspace_bytes(int M, int N, int K, int b_layout)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    if (b_layout != Q4_B_KN && b_layout != Q4_B_NK) return 0;
+    size_t bytes = align_up(4 * (static_cast<size_t>(M) + static_cast<size_t>(N)), 16);
+    if (b_layout == Q4_B_KN) bytes += static_cast<size_t>(N) * nk_pitch(K);
+    return bytes;
+}
+
+int q4_gemm(int M, int N, int K,
+            const uint8_t *A, int lda_bytes, int za,
+            const uint8_t *B, int ldb_bytes, int zb, int b_layout,
+            int32_t *C, int ldc,
+            void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!A || !B || !C) return Q4_ERR_NULL;
+    if (b_layout != Q4_B_KN && b_layout != Q4_B_NK) return Q4_ERR_LAYOUT;
+    if (M <= 0 || N <= 0 || K <= 0) return Q4_ERR_SHAPE;
+    if (lda_bytes < (K + 1) / 2 || ldc < N) return Q4_ERR_SHAPE;
+    if (ldb_bytes < (b_layout == Q4_B_KN ? (N + 1) / 2 : (K + 1) / 2)) return Q4_ERR_SHAPE;
+    if (!code_ok(za) || !code_ok(zb)) return Q4_ERR_RANGE;
+    if (K > kMaxDepth) return Q4_ERR_OVERFLOW;
+    if (reinterpret_cast<uintptr_t>(C) % 4) return Q4_ERR_ALIGN;
+    if (!workspace || workspace_bytes < q4_gemm_workspace_bytes(M, N, K, b_layout)) return Q4_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16) return Q4_ERR_ALIGN;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t *rowsumA = static_cast<int32_t *>(workspace);
+    int32_t *colsumB = rowsumA + M;
+    const uint8_t *B_nk = B;
+    long ldb_nk = ldb_bytes;
+    if (b_layout == Q4_B_KN) {
+        uint8_t *copy = static_cast<uint8_t *>(workspace) + align_up(4 * (static_cast<size_t>(M) + N), 16);
+        ldb_nk = static_cast<long>(nk_pitch(K));
+        if (q4::launch_repack_kn_to_nk(B, K, N, ldb_bytes, copy, static_cast<int>(ldb_nk), s) != hipSuccess)
+            return Q4_ERR_HIP;
+        B_nk = copy;
+    }
+    if (q4::launch_rowsum(A, M, K, lda_bytes, rowsumA, s) != hipSuccess) return Q4_ERR_HIP;
+    if (q4::launch_rowsum(B_nk, N, K, ldb_nk, colsumB, s) != hipSuccess) return Q4_ERR_HIP;
+
+    q4::GemmProblem p{};
+    p.M = M;
+    p.N = N;
+    p.K = K;
+    p.A = A;
+    p.lda = lda_bytes;
+    p.B = B_nk;
+    p.ldb = ldb_nk;
+    p.C = C;
+    p.ldc = ldc;
+    p.rowsumA = rowsumA;
+    p.colsumB = colsumB;
+    p.za = za;
+    p.zb = zb;
+    p.is_conv = false;
+    return rc_of(q4::launch_gemm(p, tile_override(), s));
+}
+
+size_t q4_conv2d_workspace_bytes(const q4_conv_desc *d)
+{
+    int OH, OW;
+    if (!d || !conv_out_dims(d, &OH, &OW)) return 0;
+    return align_up(4 * (static_cast<size_t>(d->N) * OH * OW + static_cast<size_t>(d->OC)), 16);
+}
+
+int q4_conv2d_im2col(const q4_conv_desc *d, const uint8_t *x, int zx,
+                     const uint8_t *w, int zw, const int32_t *w_colsum,
+                     int32_t *y, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!d || !x || !w || !y) return Q4_ERR_NULL;
+    int OH, OW;
+    if (!conv_out_dims(d, &OH, &OW)) return Q4_ERR_SHAPE;
+    if (!code_ok(zx) || !code_ok(zw)) return Q4_ERR_RANGE;
+    const long depth = static_cast<long>(d->KH) * d->KW * d->C;
+    if (depth > kMaxDepth) return Q4_ERR_OVERFLOW;
+    if (reinterpret_cast<uintptr_t>(y) % 4 || reinterpret_cast<uintptr_t>(w_colsum) % 4) return Q4_ERR_ALIGN;
+    if (!workspace || workspace_bytes < q4_conv2d_workspace_bytes(d)) return Q4_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16) return Q4_ERR_ALIGN;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int M = d->N * OH * OW;
+    const int K = static_cast<int>(depth);
+    int32_t *rowsum = static_cast<int32_t *>(workspace);
+    int32_t *colsum = rowsum + M;
+
+    q4::GemmProblem p{};
+    p.g.N = d->N;
+    p.g.H = d->H;
+    p.g.W = d->W;
+    p.g.C = d->C;
+    p.g.KH = d->KH;
+    p.g.KW = d->KW;
+    p.g.sh = d->stride_h;
+    p.g.sw = d->stride_w;
+    p.g.ph = d->pad_h;
+    p.g.pw = d->pad_w;
+    p.g.OH = OH;
+    p.g.OW = OW;
+    p.g.zx = zx;
+
+    if (q4::launch_conv_rowsum(x, p.g, rowsum, s) != hipSuccess) return Q4_ERR_HIP;
+    if (!w_colsum) {
+        if (q4::launch_rowsum(w, d->OC, K, (K + 1) / 2, colsum, s) != hipSuccess) return Q4_ERR_HIP;
+        w_colsum = colsum;
+    }
+    p.M = M;
+    p.N = d->OC;
+    p.K = K;
+    p.A = x;
+    p.lda = 0;
+    p.B = w;
+    p.ldb = (K + 1) / 2;
+    p.C = y;
+    p.ldc = d->OC;
+    p.rowsumA = rowsum;
+    p.colsumB = w_colsum;
+    p.za = zx;
+    p.zb = zw;
+    p.is_conv = true;
+    return rc_of(q4::launch_gemm(p, tile_override(), s));
+}
+
+int q4_requant(const int32_t *acc, long rows, int cols, long ld_acc,
+               int32_t mult, int shift, int zo, int qmin, int qmax,
+               uint8_t *out, long ld_out_bytes, void *stream)
+{
+    if (!acc || !out) return Q4_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || ld_acc < cols || ld_out_bytes < (cols + 1) / 2) return Q4_ERR_SHAPE;
+    if (mult < 0 || shift < 0 || shift > 62) return Q4_ERR_RANGE;
+    if (!code_ok(zo) || !code_ok(qmin) || !code_ok(qmax) || qmin > qmax) return Q4_ERR_RANGE;
+    if (reinterpret_cast<uintptr_t>(acc) % 4) return Q4_ERR_ALIGN;
+    return rc_of(q4::launch_requant(acc, rows, cols, ld_acc, mult, shift, zo, qmin, qmax, out, ld_out_bytes,
+                                    static_cast<hipStream_t>(stream)));
+}
+
+int q4_maxpool2x2(const uint8_t *x, int N, int H, int W, int C, uint8_t *y, void *stream)
+{
+    if (!x || !y) return Q4_ERR_NULL;
+    if (N <= 0 || H < 2 || W < 2 || C <= 0 || (C & 1)) return Q4_ERR_SHAPE;
+    return rc_of(q4::launch_maxpool2x2(x, N, H, W, C, y, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,384 @@
+// Memory-bound helper kernels of the 4-bit path for gfx950: packing, packed transpose,
+// depth sums (the correction factors of Eq. (2) of the paper), integer re-quantization
+// and 2x2 max-pool.  All are bound by HBM bandwidth; none uses the matrix cores.
+#include "q4_kernels.h"
+
+namespace q4 {
+
+namespace {
+
+constexpr uint32_t kLowNibbles = 0x0F0F0F0Fu;
+typedef int vec4i __attribute__((ext_vector_type(4)));
+
+
+// Sum of the eight codes held in one packed dword.
+__device__ __forceinline__ uint32_t nibble_sum8(uint32_t w)
+{
+    uint32_t t = (w & kLowNibbles) + ((w >> 4) & kLowNibbles);  // four byte sums, each <= 30
+    t += t >> 16;
+    t += t >> 8;
+    return t & 0xFFu;  // <= 120
+}
+
+// Bytes [b, b+4) of a row of `rowbytes` bytes, zero beyond the end; any alignment.
+__device__ __forceinline__ uint32_t load_dword_guarded(const uint8_t *row, long b, long rowbytes)
+{
+    const uint8_t *p = row + b;
+    if (b + 4 <= rowbytes && (reinterpret_cast<uintptr_t>(p) & 3u) == 0)
+        return *reinterpret_cast<const uint32_t *>(p);
+    uint32_t v = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (b + i < rowbytes) v |= static_cast<uint32_t>(p[i]) << (8 * i);
+    return v;
+}
+
+// ---------------------------------------------------------------- pack (no transpose)
+// One thread writes one output byte group of 4 (8 codes).
+__global__ void __launch_bounds__(256)
+pack_rows_kernel(const uint8_t *__restrict__ src, int rows, int cols, long ld_src,
+                 uint8_t *__restrict__ dst, long ld_dst)
+{
+    const int out_bytes = (cols + 1) >> 1;
+    const int groups = (out_bytes + 3) >> 2;
+    const long total = static_cast<long>(rows) * groups;
+    for (long idx = blockIdx.x * 256L + threadIdx.x; idx < total; idx += 256L * gridDim.x) {
+        const int r = static_cast<int>(idx / groups);
+        const int g = static_cast<int>(idx - static_cast<long>(r) * groups);
+        const uint8_t *s = src + r * ld_src + 8L * g;
+        uint8_t *d = dst + r * ld_dst + 4L * g;
+        const int c0 = 8 * g;
+        uint32_t w = 0;
+        if (c0 + 8 <= cols && (reinterpret_cast<uintptr_t>(s) & 7u) == 0) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(s);
+            const uint32_t lo = v.x & kLowNibbles, hi = v.y & kLowNibbles;
+            // bytes (c0..c3) -> nibbles
+            uint32_t a = (lo | (lo >> 4));           // byte0 = c0|c1<<4, byte2 = c2|c3<<4
+            uint32_t b = (hi | (hi >> 4));
+            w = (a & 0xFFu) | ((a >> 8) & 0xFF00u) | ((b & 0xFFu) << 16) | ((b << 8) & 0xFF000000u);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (c0 + j < cols) w |= static_cast<uint32_t>(s[j] & 15u) << (4 * j);
+        }
+        if (4 * g + 4 <= out_bytes && (reinterpret_cast<uintptr_t>(d) & 3u) == 0) {
+            *reinterpret_cast<uint32_t *>(d) = w;
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (4 * g + j < out_bytes) d[j] = static_cast<uint8_t>(w >> (8 * j));
+        }
+    }
+}
+
+// ---------------------------------------------------------------- transposing packs
+// A 64 x 64 tile of codes goes through LDS: filled along the source's contiguous
+// dimension, drained along the destination's, so both sides stay coalesced.
+constexpr int kT = 64;
+
+__device__ __forceinline__ void drain_transposed(const uint8_t (*tile)[kT + 1], int r0, int c0,
+                                                 int rows, int cols, uint8_t *dst, long ld_dst)
+{
+    // Output row = source column c, output byte j holds source rows 2j and 2j+1.
+    const int j = threadIdx.x & 31;
+    const int out_row_bytes = (rows + 1) >> 1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int c = (threadIdx.x >> 5) + 8 * i;
+        const int jb = (r0 >> 1) + j;
+        if (c0 + c < cols && jb < out_row_bytes) {
+            const uint32_t lo = tile[2 * j][c];
+            const uint32_t hi = (r0 + 2 * j + 1 < rows) ? tile[2 * j + 1][c] : 0u;
+            dst[(c0 + c) * ld_dst + jb] = static_cast<uint8_t>(lo | (hi << 4));
+        }
+    }
+}
+
+// src: rows x cols codes (one per byte) -> dst: cols rows of ceil(rows/2) bytes.
+__global__ void __launch_bounds__(256)
+pack_transpose_kernel(const uint8_t *__restrict__ src, int rows, int cols, long ld_src,
+                      uint8_t *__restrict__ dst, long ld_dst)
+{
+    __shared__ uint8_t tile[kT][kT + 1];
+    const int r0 = blockIdx.y * kT, c0 = blockIdx.x * kT;
+    const int c = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = (threadIdx.x >> 6) + 4 * i;
+        uint8_t v = 0;
+        if (r0 + r < rows && c0 + c < cols) v = src[(r0 + r) * ld_src + c0 + c] & 15u;
+        tile[r][c] = v;
+    }
+    __syncthreads();
+    drain_transposed(tile, r0, c0, rows, cols, dst, ld_dst);
+}
+
+// B_kn: K rows of ceil(N/2) bytes -> B_nk: N rows of ceil(K/2) bytes.
+__global__ void __launch_bounds__(256)
+repack_kn_to_nk_kernel(const uint8_t *__restrict__ src, int K, int N, long ld_src,
+                       uint8_t *__restrict__ dst, long ld_dst)
+{
+    __shared__ uint8_t tile[kT][kT + 1];
+    const int k0 = blockIdx.y * kT, n0 = blockIdx.x * kT;
+    const int j = threadIdx.x & 31;  // source byte within the tile row: codes n0+2j, n0+2j+1
+    const int in_row_bytes = (N + 1) >> 1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int k = (threadIdx.x >> 5) + 8 * i;
+        uint32_t w = 0;
+        const int jb = (n0 >> 1) + j;
+        if (k0 + k < K && jb < in_row_bytes) w = src[(k0 + k) * ld_src + jb];
+        tile[k][2 * j] = static_cast<uint8_t>(w & 15u);
+        tile[k][2 * j + 1] = (n0 + 2 * j + 1 < N) ? static_cast<uint8_t>(w >> 4) : uint8_t(0);
+    }
+    __syncthreads();
+    drain_transposed(tile, k0, n0, K, N, dst, ld_dst);
+}
+
+// ---------------------------------------------------------------- depth sums
+// LANES lanes cooperate on one row; a wave holds 64 / LANES rows.
+template <int LANES>
+__global__ void __launch_bounds__(256)
+rowsum_kernel(const uint8_t *__restrict__ A, int rows, int k, long ld, int32_t *__restrict__ sums)
+{
+    const int rowbytes = (k + 1) >> 1;
+    const int ndw = (rowbytes + 3) >> 2;
+    const int sub = threadIdx.x % LANES;
+    const long r = (blockIdx.x * 256L + threadIdx.x) / LANES;
+    int s = 0;
+    if (r < rows) {
+        const uint8_t *row = A + r * ld;
+        const bool fast = ((reinterpret_cast<uintptr_t>(row) & 15u) == 0) && (rowbytes % 16 == 0) && !(k & 1);
+        if (fast) {
+            const uint4 *row4 = reinterpret_cast<const uint4 *>(row);
+            for (int i = sub; i < rowbytes / 16; i += LANES) {
+                const uint4 v = row4[i];
+                s += nibble_sum8(v.x) + nibble_sum8(v.y) + nibble_sum8(v.z) + nibble_sum8(v.w);
+            }
+        } else {
+            for (int i = sub; i < ndw; i += LANES) {
+                uint32_t w = load_dword_guarded(row, 4L * i, rowbytes);
+                if (k & 1) {  // the pad nibble of an odd row is not part of the sum
+                    const int last = rowbytes - 1 - 4 * i;
+                    if (last >= 0 && last < 4) w &= ~(0xF0u << (8 * last));
+                }
+                s += nibble_sum8(w);
+            }
+        }
+    }
+#pragma unroll
+    for (int off = LANES / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (r < rows && sub == 0) sums[r] = s;
+}
+
+// Row sums of the virtual im2col matrix: one thread per output pixel, taps outside
+// the image count C * zx (they read as the zero-point code).
+__global__ void __launch_bounds__(256)
+conv_rowsum_kernel(const uint8_t *__restrict__ x, ConvGeom g, long M, int32_t *__restrict__ sums)
+{
+    const long m = blockIdx.x * 256L + threadIdx.x;
+    if (m >= M) return;
+    const int ow = static_cast<int>(m % g.OW);
+    const long t = m / g.OW;
+    const int oh = static_cast<int>(t % g.OH);
+    const long n = t / g.OH;
+    int s = 0;
+    for (int kh = 0; kh < g.KH; ++kh) {
+        const int ih = oh * g.sh + kh - g.ph;
+        for (int kw = 0; kw < g.KW; ++kw) {
+            const int iw = ow * g.sw + kw - g.pw;
+            if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) {
+                s += g.C * g.zx;
+                continue;
+            }
+            const long e0 = ((n * g.H + ih) * g.W + iw) * g.C;  // first code of the pixel
+            if ((g.C & 7) == 0 && (reinterpret_cast<uintptr_t>(x) & 3u) == 0) {
+                const uint32_t *p = reinterpret_cast<const uint32_t *>(x + (e0 >> 1));
+                for (int c = 0; c < g.C / 8; ++c) s += nibble_sum8(p[c]);
+            } else {
+                for (int c = 0; c < g.C; ++c) {
+                    const long e = e0 + c;
+                    s += (x[e >> 1] >> (4 * (e & 1))) & 15;
+                }
+            }
+        }
+    }
+    sums[m] = s;
+}
+
+// ---------------------------------------------------------------- re-quantization
+__device__ __forceinline__ uint32_t requant_one(int32_t acc, int32_t mult, int shift, int zo, int qmin, int qmax)
+{
+    // exact 64-bit product; >> on a signed 64-bit value is an arithmetic shift, i.e. floor
+    long long q = (static_cast<long long>(acc) * static_cast<long long>(mult)) >> shift;
+    q += zo;
+    q = q < qmin ? qmin : q;
+    q = q > qmax ? qmax : q;
+    return static_cast<uint32_t>(q);
+}
+
+// Fast path: one thread turns 8 accumulators (two 16-byte loads) into one packed dword.
+__global__ void __launch_bounds__(256)
+requant_vec8_kernel(const int32_t *__restrict__ acc, long rows, int cols, long ld_acc,
+                    int32_t mult, int shift, int zo, int qmin, int qmax,
+                    uint8_t *__restrict__ out, long ld_out)
+{
+    const int groups = cols >> 3;
+    const long total = rows * groups;
+    for (long idx = blockIdx.x * 256L + threadIdx.x; idx < total; idx += 256L * gridDim.x) {
+        const long r = idx / groups;
+        const int g = static_cast<int>(idx - r * groups);
+        const vec4i *p = reinterpret_cast<const vec4i *>(acc + r * ld_acc + 8L * g);
+        const vec4i v0 = __builtin_nontemporal_load(p);
+        const vec4i v1 = __builtin_nontemporal_load(p + 1);
+        uint32_t w = requant_one(v0.x, mult, shift, zo, qmin, qmax);
+        w |= requant_one(v0.y, mult, shift, zo, qmin, qmax) << 4;
+        w |= requant_one(v0.z, mult, shift, zo, qmin, qmax) << 8;
+        w |= requant_one(v0.w, mult, shift, zo, qmin, qmax) << 12;
+        w |= requant_one(v1.x, mult, shift, zo, qmin, qmax) << 16;
+        w |= requant_one(v1.y, mult, shift, zo, qmin, qmax) << 20;
+        w |= requant_one(v1.z, mult, shift, zo, qmin, qmax) << 24;
+        w |= requant_one(v1.w, mult, shift, zo, qmin, qmax) << 28;
+        *reinterpret_cast<uint32_t *>(out + r * ld_out + 4L * g) = w;
+    }
+}
+
+// Any shape and alignment: one thread per output byte.
+__global__ void __launch_bounds__(256)
+requant_generic_kernel(const int32_t *__restrict__ acc, long rows, int cols, long ld_acc,
+                       int32_t mult, int shift, int zo, int qmin, int qmax,
+                       uint8_t *__restrict__ out, long ld_out)
+{
+    const int out_bytes = (cols + 1) >> 1;
+    const long total = rows * out_bytes;
+    for (long idx = blockIdx.x * 256L + threadIdx.x; idx < total; idx += 256L * gridDim.x) {
+        const long r = idx / out_bytes;
+        const int b = static_cast<int>(idx - r * out_bytes);
+        const int32_t *p = acc + r * ld_acc + 2L * b;
+        uint32_t w = requant_one(p[0], mult, shift, zo, qmin, qmax);
+        if (2 * b + 1 < cols) w |= requant_one(p[1], mult, shift, zo, qmin, qmax) << 4;
+        out[r * ld_out + b] = static_cast<uint8_t>(w);
+    }
+}
+
+// ---------------------------------------------------------------- 2x2 max-pool
+// Per-nibble maximum of two packed words (nibbles split into two byte lanes each < 16,
+// so the borrow-free SWAR compare below is exact).
+template <typename T>
+__device__ __forceinline__ T nibble_max(T a, T b)
+{
+    constexpr T low = static_cast<T>(kLowNibbles);
+    constexpr T bit = static_cast<T>(0x10101010u);
+    T r = 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const T x = (a >> (4 * h)) & low, y = (b >> (4 * h)) & low;
+        const T ge = ((x | bit) - y) & bit;      // bit 4 of each byte set where x >= y
+        const T m = (ge >> 4) * 15;              // 0x0F where x >= y
+        r |= ((x & m) | (y & ~m & low)) << (4 * h);
+    }
+    return r;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+maxpool2x2_kernel(const uint8_t *__restrict__ x, int N, int H, int W, int Cw, uint8_t *__restrict__ y)
+{
+    // Cw = number of T-sized words per pixel.
+    const int OH = H >> 1, OW = W >> 1;
+    const long total = static_cast<long>(N) * OH * OW * Cw;
+    const T *xi = reinterpret_cast<const T *>(x);
+    T *yo = reinterpret_cast<T *>(y);
+    for (long idx = blockIdx.x * 256L + threadIdx.x; idx < total; idx += 256L * gridDim.x) {
+        const int c = static_cast<int>(idx % Cw);
+        long t = idx / Cw;
+        const int j = static_cast<int>(t % OW);
+        t /= OW;
+        const int i = static_cast<int>(t % OH);
+        const long n = t / OH;
+        const long p00 = ((n * H + 2 * i) * W + 2 * j) * Cw + c;
+        const T a = nibble_max<T>(xi[p00], xi[p00 + Cw]);
+        const T b = nibble_max<T>(xi[p00 + static_cast<long>(W) * Cw], xi[p00 + static_cast<long>(W) * Cw + Cw]);
+        yo[idx] = nibble_max<T>(a, b);
+    }
+}
+
+inline int grid_for(long work_items, int per_block = 256, int cap = 0x7fffffff)
+{
+    long g = (work_items + per_block - 1) / per_block;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return static_cast<int>(g);
+}
+
+}  // namespace
+
+hipError_t launch_pack(const uint8_t *src, int rows, int cols, int ld_src, int transpose,
+                       uint8_t *dst, int ld_dst, hipStream_t stream)
+{
+    if (!transpose) {
+        const long groups = static_cast<long>(rows) * ((((cols + 1) >> 1) + 3) >> 2);
+        pack_rows_kernel<<<grid_for(groups, 256, 1 << 16), 256, 0, stream>>>(src, rows, cols, ld_src, dst, ld_dst);
+    } else {
+        dim3 grid((cols + kT - 1) / kT, (rows + kT - 1) / kT);
+        pack_transpose_kernel<<<grid, 256, 0, stream>>>(src, rows, cols, ld_src, dst, ld_dst);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_repack_kn_to_nk(const uint8_t *B_kn, int K, int N, int ldb,
+                                  uint8_t *B_nk, int ld_out, hipStream_t stream)
+{
+    dim3 grid((N + kT - 1) / kT, (K + kT - 1) / kT);
+    repack_kn_to_nk_kernel<<<grid, 256, 0, stream>>>(B_kn, K, N, ldb, B_nk, ld_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_rowsum(const uint8_t *A, int rows, int k, long ld, int32_t *sums, hipStream_t stream)
+{
+    const int rowbytes = (k + 1) >> 1;
+    if (rowbytes >= 1024) {
+        rowsum_kernel<64><<<grid_for(static_cast<long>(rows) * 64), 256, 0, stream>>>(A, rows, k, ld, sums);
+    } else if (rowbytes >= 128) {
+        rowsum_kernel<16><<<grid_for(static_cast<long>(rows) * 16), 256, 0, stream>>>(A, rows, k, ld, sums);
+    } else {
+        rowsum_kernel<4><<<grid_for(static_cast<long>(rows) * 4), 256, 0, stream>>>(A, rows, k, ld, sums);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_rowsum(const uint8_t *x, const ConvGeom &g, int32_t *sums, hipStream_t stream)
+{
+    const long M = static_cast<long>(g.N) * g.OH * g.OW;
+    conv_rowsum_kernel<<<grid_for(M), 256, 0, stream>>>(x, g, M, sums);
+    return hipGetLastError();
+}
+
+hipError_t launch_requant(const int32_t *acc, long rows, int cols, long ld_acc,
+                          int32_t mult, int shift, int zo, int qmin, int qmax,
+                          uint8_t *out, long ld_out, hipStream_t stream)
+{
+    const bool vec = (cols % 8 == 0) && (ld_acc % 4 == 0) && (ld_out % 4 == 0) &&
+                     (reinterpret_cast<uintptr_t>(acc) % 16 == 0) && (reinterpret_cast<uintptr_t>(out) % 4 == 0);
+    if (vec) {
+        requant_vec8_kernel<<<grid_for(rows * (cols / 8), 256, 1 << 16), 256, 0, stream>>>(
+            acc, rows, cols, ld_acc, mult, shift, zo, qmin, qmax, out, ld_out);
+    } else {
+        requant_generic_kernel<<<grid_for(rows * ((cols + 1) / 2), 256, 1 << 16), 256, 0, stream>>>(
+            acc, rows, cols, ld_acc, mult, shift, zo, qmin, qmax, out, ld_out);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_maxpool2x2(const uint8_t *x, int N, int H, int W, int C, uint8_t *y, hipStream_t stream)
+{
+    const long out_px = static_cast<long>(N) * (H / 2) * (W / 2);
+    const bool aligned = (reinterpret_cast<uintptr_t>(x) % 4 == 0) && (reinterpret_cast<uintptr_t>(y) % 4 == 0);
+    if (C % 8 == 0 && aligned) {
+        maxpool2x2_kernel<uint32_t><<<grid_for(out_px * (C / 8), 256, 1 << 16), 256, 0, stream>>>(x, N, H, W, C / 8, y);
+    } else {
+        maxpool2x2_kernel<uint8_t><<<grid_for(out_px * (C / 2), 256, 1 << 16), 256, 0, stream>>>(x, N, H, W, C / 2, y);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace q4

@@ -1,0 +1,49 @@
+// Internal launch interface between the C ABI (q4_api.hip) and the gfx950 kernels.
+// Every pointer is a device pointer; every function only enqueues work on `stream`
+// and returns the hipError_t of the launch.  Arguments are already validated.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace q4 {
+
+// Geometry of a convolution seen as a GEMM over gathered patches.
+struct ConvGeom {
+    int N, H, W, C;
+    int KH, KW;
+    int sh, sw, ph, pw;
+    int OH, OW;
+    int zx;  // code read for taps outside the image
+};
+
+struct GemmProblem {
+    int M, N, K;
+    const uint8_t *A;   // dense: M rows of ceil(K/2) bytes; conv: flat packed NHWC input
+    long lda;           // bytes between rows of A (dense only)
+    const uint8_t *B;   // N rows of ceil(K/2) bytes (N x K form)
+    long ldb;           // bytes between rows of B
+    int32_t *C;         // M x N int32
+    long ldc;           // elements between rows of C
+    const int32_t *rowsumA;  // M sums of A's (virtual) rows
+    const int32_t *colsumB;  // N sums of B's rows
+    int za, zb;
+    bool is_conv;
+    ConvGeom g;         // used when is_conv
+};
+
+// Main product + zero-point epilogue: C = raw - za*colsumB[n] - zb*rowsumA[m] + K*za*zb.
+// `force_tile` < 0 picks the tile by shape; 0..2 force large / medium / small.
+hipError_t launch_gemm(const GemmProblem &p, int force_tile, hipStream_t stream);
+
+hipError_t launch_pack(const uint8_t *src, int rows, int cols, int ld_src, int transpose,
+                       uint8_t *dst, int ld_dst, hipStream_t stream);
+hipError_t launch_repack_kn_to_nk(const uint8_t *B_kn, int K, int N, int ldb,
+                                  uint8_t *B_nk, int ld_out, hipStream_t stream);
+hipError_t launch_rowsum(const uint8_t *A, int rows, int k, long ld, int32_t *sums, hipStream_t stream);
+hipError_t launch_conv_rowsum(const uint8_t *x, const ConvGeom &g, int32_t *sums, hipStream_t stream);
+hipError_t launch_requant(const int32_t *acc, long rows, int cols, long ld_acc,
+                          int32_t mult, int shift, int zo, int qmin, int qmax,
+                          uint8_t *out, long ld_out, hipStream_t stream);
+hipError_t launch_maxpool2x2(const uint8_t *x, int N, int H, int W, int C, uint8_t *y, hipStream_t stream);
+
+}  // namespace q4

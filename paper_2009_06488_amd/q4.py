@@ -1,0 +1,211 @@
+"""Thin ctypes binding over libq4.so (see include/q4.h for the contract of every call).
+
+Marshalling only: tensors are PyTorch CUDA tensors used as device memory, the
+stream is PyTorch's current stream; every step of the computation runs in the
+library's HIP kernels.  There is no CPU fallback: if the library is missing or
+a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libq4.so")
+
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_RANGE, ERR_ALIGN = -1, -2, -3, -4
+ERR_OVERFLOW, ERR_WORKSPACE, ERR_LAYOUT, ERR_HIP = -5, -6, -7, -8
+B_KN, B_NK = 0, 1
+
+EXPORTS = (
+    "q4_version", "q4_strerror", "q4_max_depth", "q4_pack", "q4_rowsum", "q4_repack_kn_to_nk",
+    "q4_gemm_workspace_bytes", "q4_gemm", "q4_conv2d_workspace_bytes", "q4_conv2d_im2col",
+    "q4_requant", "q4_maxpool2x2", "q4_debug_force_tile",
+)
+
+
+class Q4Error(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {strerror(code)} (code {code})")
+
+
+class ConvDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in
+                ("N", "H", "W", "C", "KH", "KW", "stride_h", "stride_w", "pad_h", "pad_w", "OC")]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2009_06488_amd.build` "
+            "(there is no fallback implementation)")
+    lib = ctypes.CDLL(LIB_PATH)
+    I, L, P, Z = ctypes.c_int, ctypes.c_long, ctypes.c_void_p, ctypes.c_size_t
+    lib.q4_version.restype = I
+    lib.q4_strerror.argtypes = [I]
+    lib.q4_strerror.restype = ctypes.c_char_p
+    lib.q4_max_depth.restype = I
+    lib.q4_pack.argtypes = [P, I, I, I, I, P, I, P]
+    lib.q4_rowsum.argtypes = [P, I, I, I, P, P]
+    lib.q4_repack_kn_to_nk.argtypes = [P, I, I, I, P, I, P]
+    lib.q4_gemm_workspace_bytes.argtypes = [I, I, I, I]
+    lib.q4_gemm_workspace_bytes.restype = Z
+    lib.q4_gemm.argtypes = [I, I, I, P, I, I, P, I, I, I, P, I, P, Z, P]
+    lib.q4_conv2d_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
+    lib.q4_conv2d_workspace_bytes.restype = Z
+    lib.q4_conv2d_im2col.argtypes = [ctypes.POINTER(ConvDesc), P, I, P, I, P, P, P, Z, P]
+    lib.q4_requant.argtypes = [P, L, I, L, ctypes.c_int32, I, I, I, I, P, L, P]
+    lib.q4_maxpool2x2.argtypes = [P, I, I, I, I, P, P]
+    lib.q4_debug_force_tile.argtypes = [I]
+    lib.q4_debug_force_tile.restype = None
+    return lib
+
+
+lib = _load()
+
+
+def version() -> int:
+    return int(lib.q4_version())
+
+
+def strerror(code: int) -> str:
+    return lib.q4_strerror(int(code)).decode()
+
+
+def max_depth() -> int:
+    return int(lib.q4_max_depth())
+
+
+def debug_force_tile(tile: int) -> None:
+    lib.q4_debug_force_tile(int(tile))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype) -> int:
+    if not (t.is_cuda and t.dtype == dtype):
+        raise TypeError(f"expected a CUDA tensor of {dtype}, got {t.device} {t.dtype}")
+    return t.data_ptr()
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != OK:
+        raise Q4Error(rc, what)
+
+
+def gemm_workspace_bytes(M: int, N: int, K: int, b_layout: int = B_KN) -> int:
+    return int(lib.q4_gemm_workspace_bytes(M, N, K, b_layout))
+
+
+def conv2d_workspace_bytes(desc: ConvDesc) -> int:
+    return int(lib.q4_conv2d_workspace_bytes(ctypes.byref(desc)))
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+
+
+def q4_pack(src: torch.Tensor, transpose: bool = False, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """src: rows x cols uint8 codes (row stride may exceed cols) -> packed rows."""
+    assert src.dim() == 2 and src.stride(1) == 1
+    rows, cols = src.shape
+    orows, ocols = (cols, rows) if transpose else (rows, cols)
+    if out is None:
+        out = torch.empty((orows, (ocols + 1) // 2), dtype=torch.uint8, device=src.device)
+    assert out.shape[0] == orows and out.stride(1) == 1
+    _check(lib.q4_pack(_dev(src, torch.uint8), rows, cols, src.stride(0), int(transpose),
+                       _dev(out, torch.uint8), out.stride(0), _stream()), "q4_pack")
+    return out
+
+
+def q4_rowsum(A: torch.Tensor, k: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    assert A.dim() == 2 and A.stride(1) == 1
+    if out is None:
+        out = torch.empty(A.shape[0], dtype=torch.int32, device=A.device)
+    _check(lib.q4_rowsum(_dev(A, torch.uint8), A.shape[0], k, A.stride(0), _dev(out, torch.int32), _stream()),
+           "q4_rowsum")
+    return out
+
+
+def q4_repack_kn_to_nk(B_kn: torch.Tensor, K: int, N: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    assert B_kn.dim() == 2 and B_kn.stride(1) == 1
+    if out is None:
+        out = torch.empty((N, (K + 1) // 2), dtype=torch.uint8, device=B_kn.device)
+    _check(lib.q4_repack_kn_to_nk(_dev(B_kn, torch.uint8), K, N, B_kn.stride(0),
+                                  _dev(out, torch.uint8), out.stride(0), _stream()), "q4_repack_kn_to_nk")
+    return out
+
+
+def q4_gemm(A: torch.Tensor, za: int, B: torch.Tensor, zb: int, M: int, N: int, K: int,
+            b_layout: int = B_KN, out: Optional[torch.Tensor] = None,
+            workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """A: M x ceil(K/2) packed; B: packed per b_layout -> int32 M x N."""
+    assert A.dim() == 2 and B.dim() == 2 and A.stride(1) == 1 and B.stride(1) == 1
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    need = gemm_workspace_bytes(M, N, K, b_layout)
+    if workspace is None:
+        workspace = _workspace(need, A.device)
+    _check(lib.q4_gemm(M, N, K, _dev(A, torch.uint8), A.stride(0), za,
+                       _dev(B, torch.uint8), B.stride(0), zb, b_layout,
+                       _dev(out, torch.int32), out.stride(0),
+                       _dev(workspace, torch.uint8), workspace.numel(), _stream()), "q4_gemm")
+    return out
+
+
+def conv_desc(N, H, W, C, KH, KW, stride=(1, 1), pad=(0, 0), OC=1) -> ConvDesc:
+    return ConvDesc(N, H, W, C, KH, KW, stride[0], stride[1], pad[0], pad[1], OC)
+
+
+def conv_out_hw(d: ConvDesc) -> Tuple[int, int]:
+    return ((d.H + 2 * d.pad_h - d.KH) // d.stride_h + 1, (d.W + 2 * d.pad_w - d.KW) // d.stride_w + 1)
+
+
+def q4_conv2d_im2col(desc: ConvDesc, x: torch.Tensor, zx: int, w: torch.Tensor, zw: int,
+                     w_colsum: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """x: flat packed NHWC codes; w: OC x ceil(KH*KW*C/2) packed -> int32 (N*OH*OW) x OC."""
+    assert w.is_contiguous() and x.is_contiguous()
+    OH, OW = conv_out_hw(desc)
+    if out is None:
+        out = torch.empty((desc.N * OH * OW, desc.OC), dtype=torch.int32, device=x.device)
+    assert out.is_contiguous()
+    need = conv2d_workspace_bytes(desc)
+    if workspace is None:
+        workspace = _workspace(need, x.device)
+    cs = _dev(w_colsum, torch.int32) if w_colsum is not None else None
+    _check(lib.q4_conv2d_im2col(ctypes.byref(desc), _dev(x, torch.uint8), zx, _dev(w, torch.uint8), zw, cs,
+                                _dev(out, torch.int32), _dev(workspace, torch.uint8), workspace.numel(),
+                                _stream()), "q4_conv2d_im2col")
+    return out
+
+
+def q4_requant(acc: torch.Tensor, mult: int, shift: int, zo: int, qmin: int = 0, qmax: int = 15,
+               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """acc: rows x cols int32 -> packed rows x ceil(cols/2)."""
+    assert acc.dim() == 2 and acc.stride(1) == 1
+    rows, cols = acc.shape
+    if out is None:
+        out = torch.empty((rows, (cols + 1) // 2), dtype=torch.uint8, device=acc.device)
+    assert out.stride(1) == 1
+    _check(lib.q4_requant(_dev(acc, torch.int32), rows, cols, acc.stride(0), mult, shift, zo, qmin, qmax,
+                          _dev(out, torch.uint8), out.stride(0), _stream()), "q4_requant")
+    return out
+
+
+def q4_maxpool2x2(x: torch.Tensor, N: int, H: int, W: int, C: int,
+                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """x: flat packed NHWC codes -> flat packed N x H//2 x W//2 x C codes."""
+    assert x.is_contiguous()
+    if out is None:
+        out = torch.empty((N * (H // 2) * (W // 2) * C + 1) // 2, dtype=torch.uint8, device=x.device)
+    _check(lib.q4_maxpool2x2(_dev(x, torch.uint8), N, H, W, C, _dev(out, torch.uint8), _stream()),
+           "q4_maxpool2x2")
+    return out

@@ -146,7 +146,7 @@ class CnnCase:
 
 
 CNN_CHANNELS = (16, 32, 32, 64, 64, 128)
-CNN_SHIFTS = (18, 20, 21, 21, 21, 21)
+CNN_SHIFTS = (18, 20, 22, 22, 22, 22)
 CNN_POOL_AFTER = (False, True, False, True, False, False)
 
 

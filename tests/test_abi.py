@@ -1,0 +1,99 @@
+"""Host-only checks of the C ABI: the library loads, exports what include/q4.h declares,
+and turns bad arguments into error codes before any GPU call (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "q4.h")
+
+q4 = pytest.importorskip("paper_2009_06488_amd.q4", reason="libq4.so not built")
+
+FAKE = 0x10000  # a non-NULL, 16-byte aligned address that is never dereferenced on these paths
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(q4_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = _declared_functions()
+    assert {"q4_pack", "q4_gemm", "q4_conv2d_im2col", "q4_requant"} <= set(names)
+    for n in names:
+        assert hasattr(q4.lib, n), f"{n} declared in include/q4.h but not exported"
+    assert set(q4.EXPORTS) == set(names)
+
+
+def test_version_strerror_max_depth():
+    assert q4.version() >= 100
+    assert q4.max_depth() == (2 ** 31 - 1) // 225 == 9544371
+    assert q4.strerror(0) == "ok"
+    for code in range(-8, 0):
+        assert q4.strerror(code) not in ("ok", "unknown error code")
+    assert q4.strerror(-99) == "unknown error code"
+
+
+def test_workspace_queries():
+    assert q4.gemm_workspace_bytes(64, 32, 72, q4.B_NK) == 4 * 96
+    assert q4.gemm_workspace_bytes(64, 32, 72, q4.B_KN) == 4 * 96 + 32 * 48      # rows of 36 bytes padded to 48
+    assert q4.gemm_workspace_bytes(0, 32, 72, q4.B_NK) == 0
+    assert q4.gemm_workspace_bytes(1, 1, 1, 5) == 0
+    d = q4.conv_desc(1, 64, 64, 32, 3, 3, (1, 1), (1, 1), 64)
+    assert q4.conv2d_workspace_bytes(d) == 4 * (4096 + 64)
+    assert q4.conv2d_workspace_bytes(q4.conv_desc(1, 2, 2, 1, 3, 3, (1, 1), (0, 0), 1)) == 0   # kernel larger than image
+
+
+def _gemm(M=4, N=4, K=8, A=FAKE, lda=4, za=0, B=FAKE, ldb=4, zb=0, layout=1, C=FAKE, ldc=4, ws=FAKE, wsb=1 << 20):
+    return q4.lib.q4_gemm(M, N, K, A, lda, za, B, ldb, zb, layout, C, ldc, ws, wsb, None)
+
+
+def test_gemm_argument_errors():
+    assert _gemm(A=None) == q4.ERR_NULL
+    assert _gemm(B=None) == q4.ERR_NULL
+    assert _gemm(C=None) == q4.ERR_NULL
+    assert _gemm(layout=2) == q4.ERR_LAYOUT
+    assert _gemm(M=0) == q4.ERR_SHAPE
+    assert _gemm(K=-1) == q4.ERR_SHAPE
+    assert _gemm(lda=3) == q4.ERR_SHAPE
+    assert _gemm(ldb=3) == q4.ERR_SHAPE
+    assert _gemm(layout=0, N=9, ldc=9, ldb=4) == q4.ERR_SHAPE     # K x N layout needs ceil(9/2) = 5 bytes
+    assert _gemm(ldc=3) == q4.ERR_SHAPE
+    assert _gemm(za=16) == q4.ERR_RANGE
+    assert _gemm(zb=-1) == q4.ERR_RANGE
+    big = q4.max_depth() + 1
+    assert _gemm(K=big, lda=big, ldb=big) == q4.ERR_OVERFLOW
+    assert _gemm(C=FAKE + 2) == q4.ERR_ALIGN
+    assert _gemm(ws=None) == q4.ERR_WORKSPACE
+    assert _gemm(wsb=8) == q4.ERR_WORKSPACE
+    assert _gemm(ws=FAKE + 4) == q4.ERR_ALIGN
+
+
+def test_other_argument_errors():
+    L = q4.lib
+    assert L.q4_pack(None, 1, 1, 1, 0, FAKE, 1, None) == q4.ERR_NULL
+    assert L.q4_pack(FAKE, 0, 1, 1, 0, FAKE, 1, None) == q4.ERR_SHAPE
+    assert L.q4_pack(FAKE, 2, 8, 7, 0, FAKE, 4, None) == q4.ERR_SHAPE
+    assert L.q4_pack(FAKE, 2, 8, 8, 0, FAKE, 3, None) == q4.ERR_SHAPE
+    assert L.q4_pack(FAKE, 3, 8, 8, 1, FAKE, 1, None) == q4.ERR_SHAPE       # transposed rows hold ceil(3/2) bytes
+    assert L.q4_rowsum(FAKE, 1, 8, 3, FAKE, None) == q4.ERR_SHAPE
+    assert L.q4_rowsum(FAKE, 1, 8, 4, None, None) == q4.ERR_NULL
+    assert L.q4_repack_kn_to_nk(FAKE, 8, 8, 3, FAKE, 4, None) == q4.ERR_SHAPE
+    assert L.q4_requant(FAKE, 1, 8, 8, -1, 20, 8, 0, 15, FAKE, 4, None) == q4.ERR_RANGE
+    assert L.q4_requant(FAKE, 1, 8, 8, 1, 63, 8, 0, 15, FAKE, 4, None) == q4.ERR_RANGE
+    assert L.q4_requant(FAKE, 1, 8, 8, 1, 20, 16, 0, 15, FAKE, 4, None) == q4.ERR_RANGE
+    assert L.q4_requant(FAKE, 1, 8, 8, 1, 20, 8, 9, 8, FAKE, 4, None) == q4.ERR_RANGE
+    assert L.q4_requant(FAKE, 1, 8, 7, 1, 20, 8, 0, 15, FAKE, 4, None) == q4.ERR_SHAPE
+    assert L.q4_requant(FAKE, 1, 8, 8, 1, 20, 8, 0, 15, None, 4, None) == q4.ERR_NULL
+    assert L.q4_maxpool2x2(FAKE, 1, 4, 4, 3, FAKE, None) == q4.ERR_SHAPE    # odd channel count
+    assert L.q4_maxpool2x2(FAKE, 1, 1, 4, 2, FAKE, None) == q4.ERR_SHAPE
+    d = q4.conv_desc(1, 8, 8, 4, 3, 3, (1, 1), (1, 1), 4)
+    ref = ctypes.byref(d)
+    assert L.q4_conv2d_im2col(None, FAKE, 0, FAKE, 0, None, FAKE, FAKE, 1 << 20, None) == q4.ERR_NULL
+    assert L.q4_conv2d_im2col(ref, FAKE, 16, FAKE, 0, None, FAKE, FAKE, 1 << 20, None) == q4.ERR_RANGE
+    assert L.q4_conv2d_im2col(ref, FAKE, 0, FAKE, 0, None, FAKE, FAKE, 16, None) == q4.ERR_WORKSPACE
+    bad = q4.conv_desc(1, 8, 8, 4, 3, 3, (0, 1), (1, 1), 4)
+    assert L.q4_conv2d_im2col(ctypes.byref(bad), FAKE, 0, FAKE, 0, None, FAKE, FAKE, 1 << 20, None) == q4.ERR_SHAPE

@@ -1,0 +1,389 @@
+"""GPU parity: every libq4 call, through the C ABI, against the CPU oracle, bit for bit.
+
+All inputs are seeded and synthetic (paper_2009_06488_amd.workloads); expected values
+come from oracle/ only.  Each case prints its name before touching the GPU.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import q4_oracle as o
+from paper_2009_06488_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+from paper_2009_06488_amd import q4  # noqa: E402  (fails loudly if libq4.so is missing)
+
+DEV = torch.device("cuda:0")
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def flat_pack(codes):
+    return o.pack(np.ascontiguousarray(codes).reshape(1, -1)).reshape(-1)
+
+
+# ------------------------------------------------------------------ pack / repack / sums
+@pytest.mark.parametrize("rows,cols", [(1, 1), (1, 2), (3, 7), (5, 8), (64, 72), (72, 32), (33, 65),
+                                       (128, 129), (257, 300), (1024, 1152)])
+def test_pack(rows, cols):
+    say("pack", rows, cols)
+    rng = np.random.default_rng(rows * 7 + cols)
+    codes = rng.integers(0, 256, size=(rows, cols), dtype=np.uint8)     # upper bits must be masked off
+    for tr in (False, True):
+        got = host(q4.q4_pack(dev(codes), transpose=tr))
+        assert np.array_equal(got, o.pack(codes, transpose=tr)), (rows, cols, tr)
+
+
+def test_pack_strided_source_and_padded_rows():
+    say("pack strided")
+    rng = np.random.default_rng(1)
+    big = rng.integers(0, 16, size=(20, 50), dtype=np.uint8)
+    src = dev(big)[:, 3:40]                      # ld_src = 50, unaligned start
+    out = torch.full((20, 32), 0xEE, dtype=torch.uint8, device=DEV)
+    q4.q4_pack(src, out=out[:, :19])             # ld_dst = 32 > 19
+    got = host(out)
+    assert np.array_equal(got[:, :19], o.pack(big[:, 3:40]))
+    assert np.all(got[:, 19:] == 0xEE)           # bytes beyond the row are untouched
+
+
+@pytest.mark.parametrize("K,N", [(1, 1), (2, 2), (7, 5), (72, 32), (64, 64), (65, 63), (288, 256), (1152, 1024), (130, 257)])
+def test_repack_kn_to_nk(K, N):
+    say("repack", K, N)
+    rng = np.random.default_rng(K * 13 + N)
+    b = rng.integers(0, 16, size=(K, N), dtype=np.uint8)
+    got = host(q4.q4_repack_kn_to_nk(dev(o.pack(b)), K, N))
+    assert np.array_equal(got, o.pack(b, transpose=True))
+
+
+@pytest.mark.parametrize("rows,k", [(1, 1), (3, 2), (5, 9), (64, 72), (32, 73), (17, 288), (300, 1152),
+                                    (9, 4096), (130, 8192), (2, 100001)])
+def test_rowsum(rows, k):
+    say("rowsum", rows, k)
+    rng = np.random.default_rng(rows + k)
+    codes = rng.integers(0, 16, size=(rows, k), dtype=np.uint8)
+    packed = o.pack(codes)
+    if k % 2:
+        packed[:, -1] |= 0xF0                    # the pad nibble must be ignored
+    got = host(q4.q4_rowsum(dev(packed), k))
+    assert np.array_equal(got, codes.astype(np.int64).sum(1))
+    assert np.array_equal(got, o.rowsum(o.pack(codes), k))
+
+
+# ------------------------------------------------------------------ GEMM
+def run_gemm_case(a_codes, b_codes, za, zb, layouts=(q4.B_KN, q4.B_NK), tiles=(-1,), dirty_pad=False):
+    M, K = a_codes.shape
+    N = b_codes.shape[1]
+    A = o.pack(a_codes)
+    Bkn = o.pack(b_codes)
+    Bnk = o.pack(b_codes, transpose=True)
+    want = o.gemm(A, za, Bkn, zb, M, N, K, o.B_KN)
+    if dirty_pad and K % 2:
+        A = A.copy()
+        Bnk = Bnk.copy()
+        A[:, -1] |= 0xF0
+        Bnk[:, -1] |= 0xF0
+    dA, dBkn, dBnk = dev(A), dev(Bkn), dev(Bnk)
+    for tile in tiles:
+        q4.debug_force_tile(tile)
+        try:
+            for layout in layouts:
+                got = host(q4.q4_gemm(dA, za, dBkn if layout == q4.B_KN else dBnk, zb, M, N, K, layout))
+                bad = np.argwhere(got != want)
+                assert bad.size == 0, (M, N, K, za, zb, layout, tile, bad[:5].tolist(),
+                                       got[tuple(bad[0])], want[tuple(bad[0])])
+        finally:
+            q4.debug_force_tile(-1)
+
+
+def test_gemm_handworked(golden):
+    say("gemm handworked 2x2x2")
+    g = golden("handworked.txt")
+    A = dev(np.array(g["gemm_a_packed"], dtype=np.uint8))
+    for layout, key in ((q4.B_KN, "gemm_b_packed_kn"), (q4.B_NK, "gemm_b_packed_nk")):
+        B = dev(np.array(g[key], dtype=np.uint8))
+        assert host(q4.q4_gemm(A, g["gemm_za"], B, g["gemm_zb"], 2, 2, 2, layout)).tolist() == g["gemm_c"]
+
+
+def test_gemm_config1():
+    c = wl.config1()
+    say(c.name)
+    run_gemm_case(c.a_codes, c.b_codes, c.za, c.zb, tiles=(-1, 0, 1, 2))
+
+
+@pytest.mark.parametrize("idx", range(27))
+def test_gemm_config2(idx):
+    M, N, K, seed = wl.config2_shapes()[idx]
+    c = wl.gemm_case(f"cfg2_{M}x{N}x{K}", M, N, K, seed)
+    say(c.name, "za", c.za, "zb", c.zb)
+    run_gemm_case(c.a_codes, c.b_codes, c.za, c.zb, tiles=(-1,) if M * N > 256 * 256 else (-1, 0, 1, 2))
+
+
+ODD_SHAPES = [(1, 1, 1), (1, 1, 2), (2, 3, 1), (3, 2, 9), (15, 17, 31), (16, 16, 32), (17, 15, 33),
+              (31, 33, 63), (33, 31, 64), (63, 65, 65), (65, 63, 127), (64, 64, 128), (64, 64, 129),
+              (100, 7, 255), (7, 100, 257), (129, 130, 200), (257, 255, 96), (300, 200, 513), (1, 300, 1000),
+              (300, 1, 1001)]
+
+
+@pytest.mark.parametrize("M,N,K", ODD_SHAPES)
+def test_gemm_ragged_shapes(M, N, K):
+    say("gemm ragged", M, N, K)
+    rng = np.random.default_rng(M * 10007 + N * 101 + K)
+    za, zb = (int(v) for v in rng.integers(0, 16, size=2))
+    a = rng.integers(0, 16, size=(M, K), dtype=np.uint8)
+    b = rng.integers(0, 16, size=(K, N), dtype=np.uint8)
+    run_gemm_case(a, b, za, zb, tiles=(-1, 0, 1, 2), dirty_pad=True)
+
+
+@pytest.mark.parametrize("za,zb,fa,fb", [(0, 0, 15, 15), (15, 15, 0, 0), (0, 15, 15, 0), (15, 0, 0, 15), (7, 3, 7, 15), (3, 8, 15, 8)])
+def test_gemm_extremes(za, zb, fa, fb):
+    say("gemm extremes", za, zb, fa, fb)
+    M, N, K = 70, 40, 8192
+    a = np.full((M, K), fa, np.uint8)
+    b = np.full((K, N), fb, np.uint8)
+    run_gemm_case(a, b, za, zb, layouts=(q4.B_NK,))
+    got_const = (fa - za) * (fb - zb) * K
+    assert abs(got_const) <= 225 * K
+
+
+def test_gemm_unaligned_views_and_ldc():
+    say("gemm unaligned views")
+    rng = np.random.default_rng(99)
+    M, N, K = 77, 45, 150
+    a = rng.integers(0, 16, size=(M, K), dtype=np.uint8)
+    b = rng.integers(0, 16, size=(K, N), dtype=np.uint8)
+    A, Bnk = o.pack(a), o.pack(b, transpose=True)
+    want = o.gemm(A, 5, Bnk, 9, M, N, K, o.B_NK)
+    bufA = torch.zeros((M, 100), dtype=torch.uint8, device=DEV)
+    bufB = torch.zeros((N, 90), dtype=torch.uint8, device=DEV)
+    bufA[:, 3:78] = dev(A)
+    bufB[:, 1:76] = dev(Bnk)
+    out = torch.full((M, 64), -7, dtype=torch.int32, device=DEV)
+    q4.q4_gemm(bufA[:, 3:78], 5, bufB[:, 1:76], 9, M, N, K, q4.B_NK, out=out[:, :N])
+    got = host(out)
+    assert np.array_equal(got[:, :N], want)
+    assert np.all(got[:, N:] == -7)
+
+
+def test_gemm_is_deterministic_across_tiles():
+    say("gemm determinism")
+    c = wl.gemm_case("det", 512, 384, 1152, seed=123)
+    A, B = dev(o.pack(c.a_codes)), dev(o.pack(c.b_codes, transpose=True))
+    outs = []
+    for tile in (0, 1, 2, 0):
+        q4.debug_force_tile(tile)
+        outs.append(host(q4.q4_gemm(A, c.za, B, c.zb, c.M, c.N, c.K, q4.B_NK)).copy())
+    q4.debug_force_tile(-1)
+    for x in outs[1:]:
+        assert np.array_equal(outs[0], x)
+    assert np.array_equal(outs[0], o.gemm_f64(o.pack(c.a_codes), c.za, o.pack(c.b_codes), c.zb, c.M, c.N, c.K))
+
+
+# ------------------------------------------------------------------ convolution / requant / pool
+def run_conv_case(c, tiles=(-1,)):
+    x = flat_pack(c.x_codes)
+    w = o.pack(c.w_codes.reshape(c.OC, -1))
+    want = o.conv2d(x, c.zx, w, c.zw, c.N, c.H, c.W, c.C, c.KH, c.KW, c.stride, c.pad, c.OC)
+    d = q4.conv_desc(c.N, c.H, c.W, c.C, c.KH, c.KW, c.stride, c.pad, c.OC)
+    dx, dw = dev(x), dev(w)
+    for tile in tiles:
+        q4.debug_force_tile(tile)
+        try:
+            got = host(q4.q4_conv2d_im2col(d, dx, c.zx, dw, c.zw))
+        finally:
+            q4.debug_force_tile(-1)
+        bad = np.argwhere(got != want)
+        assert bad.size == 0, (c.name, tile, bad[:5].tolist())
+    # precomputed weight sums give the same result
+    cs = q4.q4_rowsum(dw, c.depth)
+    assert np.array_equal(host(q4.q4_conv2d_im2col(d, dx, c.zx, dw, c.zw, w_colsum=cs)), want)
+    return want
+
+
+def test_conv_handworked(golden):
+    say("conv handworked 3x3")
+    g = golden("handworked.txt")
+    x = np.array(g["conv_x"], dtype=np.uint8).reshape(1, 3, 3, 1)
+    w = np.array(g["conv_w"], dtype=np.uint8).reshape(1, 9)
+    d = q4.conv_desc(1, 3, 3, 1, 3, 3, (1, 1), (1, 1), 1)
+    got = host(q4.q4_conv2d_im2col(d, dev(flat_pack(x)), g["conv_zx"], dev(o.pack(w)), g["conv_zw"]))
+    assert got.reshape(3, 3).tolist() == g["conv_y"]
+
+
+def test_conv_config3_then_requant():
+    c = wl.config3()
+    say(c.name)
+    want = run_conv_case(c, tiles=(-1, 0, 1, 2))
+    wantq = o.requant(want, c.mult, c.shift, c.zo)
+    gotq = host(q4.q4_requant(dev(want), c.mult, c.shift, c.zo))
+    assert np.array_equal(gotq, wantq)
+    hist = np.bincount(o.unpack(wantq.reshape(-1), want.size), minlength=16)
+    assert hist[1:15].sum() > 0.5 * want.size           # the constants do not saturate the layer
+
+
+CONV_CASES = [
+    # N, H, W, C, KH, KW, stride, pad, OC
+    (1, 5, 5, 1, 3, 3, (1, 1), (1, 1), 2),
+    (2, 6, 7, 3, 3, 3, (1, 1), (0, 0), 4),
+    (1, 9, 8, 2, 5, 5, (1, 1), (0, 0), 3),
+    (2, 9, 11, 4, 3, 3, (2, 2), (0, 0), 5),
+    (1, 8, 10, 5, 3, 2, (2, 1), (1, 0), 3),
+    (1, 7, 7, 8, 1, 1, (1, 1), (0, 0), 6),
+    (1, 6, 6, 32, 3, 3, (1, 1), (1, 1), 8),
+    (1, 4, 9, 1, 3, 3, (1, 1), (2, 3), 2),
+    (3, 12, 20, 16, 3, 3, (1, 1), (1, 1), 32),
+    (2, 10, 12, 64, 3, 3, (1, 1), (1, 1), 70),
+    (1, 17, 13, 32, 3, 3, (2, 2), (1, 1), 33),
+    (1, 25, 33, 1, 5, 5, (1, 1), (0, 0), 8),     # first layer of the paper's CNN (Table 2)
+    (1, 19, 27, 8, 3, 3, (2, 2), (0, 0), 8),     # its third layer: stride 2, no padding
+]
+
+
+@pytest.mark.parametrize("N,H,W,C,KH,KW,stride,pad,OC", CONV_CASES)
+def test_conv_shapes(N, H, W, C, KH, KW, stride, pad, OC):
+    say("conv", N, H, W, C, KH, KW, stride, pad, OC)
+    c = wl.conv_case("t", N, H, W, C, KH, KW, stride, pad, OC, zx=(H + C) % 16, zw=(W + OC) % 16,
+                     shift=20, zo=8, seed=H * 1000 + W * 10 + C)
+    run_conv_case(c, tiles=(-1, 1))
+
+
+def test_conv_equals_explicit_im2col_gemm_on_gpu():
+    say("conv vs explicit im2col gemm")
+    c = wl.conv_case("t", 2, 9, 7, 32, 3, 3, (1, 1), (1, 1), 48, zx=6, zw=9, shift=20, zo=8, seed=5)
+    xp = np.full((c.N, c.H + 2, c.W + 2, c.C), c.zx, dtype=np.uint8)
+    xp[:, 1:-1, 1:-1, :] = c.x_codes
+    rows = [xp[n, i:i + 3, j:j + 3, :].reshape(-1) for n in range(c.N) for i in range(c.H) for j in range(c.W)]
+    a = np.stack(rows)
+    w = o.pack(c.w_codes.reshape(c.OC, -1))
+    d = q4.conv_desc(c.N, c.H, c.W, c.C, 3, 3, (1, 1), (1, 1), c.OC)
+    y1 = host(q4.q4_conv2d_im2col(d, dev(flat_pack(c.x_codes)), c.zx, dev(w), c.zw))
+    y2 = host(q4.q4_gemm(dev(o.pack(a)), c.zx, dev(w), c.zw, a.shape[0], c.OC, a.shape[1], q4.B_NK))
+    assert np.array_equal(y1, y2)
+
+
+@pytest.mark.parametrize("rows,cols", [(1, 1), (3, 5), (7, 8), (64, 64), (4096, 64), (33, 130), (1000, 16)])
+def test_requant(rows, cols):
+    say("requant", rows, cols)
+    rng = np.random.default_rng(rows * 3 + cols)
+    acc = rng.integers(-400000, 400000, size=(rows, cols), dtype=np.int64).astype(np.int32)
+    acc.flat[0] = -2 ** 31
+    acc.flat[-1] = 2 ** 31 - 1
+    for mult, shift, zo, qmin, qmax in [(24576, 20, 8, 0, 15), (2 ** 31 - 1, 62, 0, 0, 15), (1, 0, 15, 3, 12),
+                                        (0, 5, 9, 0, 15), (31000, 18, 8, 8, 15)]:
+        got = host(q4.q4_requant(dev(acc), mult, shift, zo, qmin, qmax))
+        assert np.array_equal(got, o.requant(acc, mult, shift, zo, qmin, qmax)), (mult, shift)
+
+
+def test_requant_handworked(golden):
+    say("requant handworked")
+    g = golden("handworked.txt")
+    for mult, acc, want in g["requant_a"] + g["requant_b"]:
+        got = host(q4.q4_requant(dev(np.array([[acc]], dtype=np.int32)), mult, 20, 8))
+        assert int(got[0, 0]) == want
+
+
+@pytest.mark.parametrize("N,H,W,C", [(1, 2, 2, 2), (2, 4, 6, 6), (1, 5, 7, 2), (3, 8, 8, 16), (2, 32, 128, 32), (1, 9, 10, 24)])
+def test_maxpool(N, H, W, C):
+    say("maxpool", N, H, W, C)
+    rng = np.random.default_rng(H * 10 + W + C)
+    x = rng.integers(0, 16, size=(N, H, W, C), dtype=np.uint8)
+    xp = flat_pack(x)
+    got = host(q4.q4_maxpool2x2(dev(xp), N, H, W, C))
+    assert np.array_equal(got, o.maxpool2x2(xp, N, H, W, C))
+
+
+# ------------------------------------------------------------------ config 4: the OCR-style CNN
+def cnn_forward_oracle(case, x_codes):
+    """Layer by layer with oracle calls only."""
+    N, H, W = x_codes.shape[0], case.H, case.W
+    act, zx, cin = flat_pack(x_codes), case.zx, 1
+    for L in case.layers:
+        w = o.pack(L.w_codes.reshape(L.cout, -1))
+        y = o.conv2d(act, zx, w, L.zw, N, H, W, cin, 3, 3, (1, 1), (case.pad, case.pad), L.cout)
+        H, W = H + 2 * case.pad - 2, W + 2 * case.pad - 2
+        act = o.requant(y, L.mult, L.shift, L.zo).reshape(-1)
+        zx, cin = L.zo, L.cout
+        if L.pool_after:
+            act = o.maxpool2x2(act, N, H, W, cin)
+            H, W = H // 2, W // 2
+    return act, (N, H, W, cin)
+
+
+def cnn_forward_gpu(case, x_codes):
+    N, H, W = x_codes.shape[0], case.H, case.W
+    act, zx, cin = dev(flat_pack(x_codes)), case.zx, 1
+    for L in case.layers:
+        w = dev(o.pack(L.w_codes.reshape(L.cout, -1)))
+        d = q4.conv_desc(N, H, W, cin, 3, 3, (1, 1), (case.pad, case.pad), L.cout)
+        y = q4.q4_conv2d_im2col(d, act, zx, w, L.zw)
+        H, W = q4.conv_out_hw(d)
+        act = q4.q4_requant(y, L.mult, L.shift, L.zo).reshape(-1)
+        zx, cin = L.zo, L.cout
+        if L.pool_after:
+            act = q4.q4_maxpool2x2(act, N, H, W, cin)
+            H, W = H // 2, W // 2
+    return host(act), (N, H, W, cin)
+
+
+@pytest.mark.parametrize("pad", [1, 0])
+def test_cnn_config4_small_batch(pad):
+    case = wl.config4(batch=2, pad=pad)
+    say(case.name, "pad", pad)
+    want, shape_w = cnn_forward_oracle(case, case.x_codes)
+    got, shape_g = cnn_forward_gpu(case, case.x_codes)
+    assert shape_w == shape_g == ((2, 8, 32, 128) if pad == 1 else (2, 1, 25, 128))
+    assert np.array_equal(got, want)
+    hist = np.bincount(o.unpack(want, want.size * 2), minlength=16)
+    assert hist[1:15].sum() > 0.3 * want.size * 2       # the last layer is not saturated
+
+
+def test_cnn_config4_full_batch_sampled_images():
+    """Batch 64 on the GPU; the oracle recomputes images 0, 31 and 63 on their own (images are independent)."""
+    case = wl.config4(batch=64)
+    say(case.name, "full batch, sampled images")
+    got, (N, H, W, C) = cnn_forward_gpu(case, case.x_codes)
+    per = H * W * C // 2
+    for img in (0, 31, 63):
+        want, _ = cnn_forward_oracle(case, case.x_codes[img:img + 1])
+        assert np.array_equal(got[img * per:(img + 1) * per], want), img
+
+
+# ------------------------------------------------------------------ config 5: the large GEMM
+def test_gemm_config5_full_size():
+    """8192^3 in the configuration the benchmark times.  Every element is compared with the BLAS
+    float64 form of the oracle (exact); 48 sampled rows are also recomputed by the plain loops."""
+    c = wl.config5()
+    say(c.name)
+    A, Bkn = dev(c.a_packed), dev(c.b_packed_kn)
+    Bnk = q4.q4_repack_kn_to_nk(Bkn, c.K, c.N)
+    got_nk = host(q4.q4_gemm(A, c.za, Bnk, c.zb, c.M, c.N, c.K, q4.B_NK))
+    got_kn = host(q4.q4_gemm(A, c.za, Bkn, c.zb, c.M, c.N, c.K, q4.B_KN))
+    assert np.array_equal(got_nk, got_kn)
+    say("config5 oracle rows")
+    rows = np.random.default_rng(1).choice(c.M, size=48, replace=False)
+    rows[:2] = (0, c.M - 1)
+    want_rows = o.gemm_rows(c.a_packed, c.za, c.b_packed_kn, c.zb, rows, c.N, c.K, o.B_KN)
+    assert np.array_equal(got_nk[rows], want_rows)
+    say("config5 oracle float64 full")
+    slab = 2048
+    for r0 in range(0, c.M, slab):
+        want = o.gemm_f64(c.a_packed[r0:r0 + slab], c.za, c.b_packed_kn, c.zb, slab, c.N, c.K, o.B_KN)
+        assert np.array_equal(got_nk[r0:r0 + slab], want), r0
+        say("config5 slab ok", r0)
