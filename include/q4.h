@@ -119,6 +119,20 @@ int q4_gemm(int M, int N, int K,
             int32_t *C, int ldc,
             void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * q4_gemm_presummed -- the product and epilogue of q4_gemm alone, for callers
+ * that already hold the depth sums (weights: computed once with the layer,
+ * Sec. 3.2; activations: from q4_rowsum or a producer that emits them).
+ *   B_nk    : N rows of ceil(K/2) bytes (Q4_B_NK form).
+ *   rowsumA : M int32, rowsumA[m] = sum_k A[m,k]  (what q4_rowsum(A, M, K) returns).
+ *   colsumB : N int32, colsumB[n] = sum_k B[k,n]  (what q4_rowsum(B_nk, N, K) returns).
+ * Launches exactly one kernel and needs no workspace.
+ */
+int q4_gemm_presummed(int M, int N, int K,
+                      const uint8_t *A, int lda_bytes, int za, const int32_t *rowsumA,
+                      const uint8_t *B_nk, int ldb_bytes, int zb, const int32_t *colsumB,
+                      int32_t *C, int ldc, void *stream);
+
 typedef struct {
     int N, H, W, C;         /* input: batch, height, width, channels (NHWC) */
     int KH, KW;             /* kernel size */

@@ -156,6 +156,37 @@ int q4_gemm(int M, int N, int K,
     return rc_of(q4::launch_gemm(p, tile_override(), s));
 }
 
+int q4_gemm_presummed(int M, int N, int K,
+                      const uint8_t *A, int lda_bytes, int za, const int32_t *rowsumA,
+                      const uint8_t *B_nk, int ldb_bytes, int zb, const int32_t *colsumB,
+                      int32_t *C, int ldc, void *stream)
+{
+    if (!A || !B_nk || !C || !rowsumA || !colsumB) return Q4_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0) return Q4_ERR_SHAPE;
+    if (lda_bytes < (K + 1) / 2 || ldb_bytes < (K + 1) / 2 || ldc < N) return Q4_ERR_SHAPE;
+    if (!code_ok(za) || !code_ok(zb)) return Q4_ERR_RANGE;
+    if (K > kMaxDepth) return Q4_ERR_OVERFLOW;
+    if (reinterpret_cast<uintptr_t>(C) % 4 || reinterpret_cast<uintptr_t>(rowsumA) % 4 ||
+        reinterpret_cast<uintptr_t>(colsumB) % 4)
+        return Q4_ERR_ALIGN;
+    q4::GemmProblem p{};
+    p.M = M;
+    p.N = N;
+    p.K = K;
+    p.A = A;
+    p.lda = lda_bytes;
+    p.B = B_nk;
+    p.ldb = ldb_bytes;
+    p.C = C;
+    p.ldc = ldc;
+    p.rowsumA = rowsumA;
+    p.colsumB = colsumB;
+    p.za = za;
+    p.zb = zb;
+    p.is_conv = false;
+    return rc_of(q4::launch_gemm(p, tile_override(), static_cast<hipStream_t>(stream)));
+}
+
 size_t q4_conv2d_workspace_bytes(const q4_conv_desc *d)
 {
     int OH, OW;

@@ -23,7 +23,7 @@ B_KN, B_NK = 0, 1
 
 EXPORTS = (
     "q4_version", "q4_strerror", "q4_max_depth", "q4_pack", "q4_rowsum", "q4_repack_kn_to_nk",
-    "q4_gemm_workspace_bytes", "q4_gemm", "q4_conv2d_workspace_bytes", "q4_conv2d_im2col",
+    "q4_gemm_workspace_bytes", "q4_gemm", "q4_gemm_presummed", "q4_conv2d_workspace_bytes", "q4_conv2d_im2col",
     "q4_requant", "q4_maxpool2x2", "q4_debug_force_tile",
 )
 
@@ -56,6 +56,7 @@ def _load() -> ctypes.CDLL:
     lib.q4_gemm_workspace_bytes.argtypes = [I, I, I, I]
     lib.q4_gemm_workspace_bytes.restype = Z
     lib.q4_gemm.argtypes = [I, I, I, P, I, I, P, I, I, I, P, I, P, Z, P]
+    lib.q4_gemm_presummed.argtypes = [I, I, I, P, I, I, P, P, I, I, P, P, I, P]
     lib.q4_conv2d_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
     lib.q4_conv2d_workspace_bytes.restype = Z
     lib.q4_conv2d_im2col.argtypes = [ctypes.POINTER(ConvDesc), P, I, P, I, P, P, P, Z, P]
@@ -157,6 +158,19 @@ def q4_gemm(A: torch.Tensor, za: int, B: torch.Tensor, zb: int, M: int, N: int, 
                        _dev(B, torch.uint8), B.stride(0), zb, b_layout,
                        _dev(out, torch.int32), out.stride(0),
                        _dev(workspace, torch.uint8), workspace.numel(), _stream()), "q4_gemm")
+    return out
+
+
+def q4_gemm_presummed(A: torch.Tensor, za: int, rowsumA: torch.Tensor, B_nk: torch.Tensor, zb: int,
+                      colsumB: torch.Tensor, M: int, N: int, K: int,
+                      out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Product + epilogue only (one kernel), with the depth sums supplied by the caller."""
+    assert A.dim() == 2 and B_nk.dim() == 2 and A.stride(1) == 1 and B_nk.stride(1) == 1
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _check(lib.q4_gemm_presummed(M, N, K, _dev(A, torch.uint8), A.stride(0), za, _dev(rowsumA, torch.int32),
+                                 _dev(B_nk, torch.uint8), B_nk.stride(0), zb, _dev(colsumB, torch.int32),
+                                 _dev(out, torch.int32), out.stride(0), _stream()), "q4_gemm_presummed")
     return out
 
 
