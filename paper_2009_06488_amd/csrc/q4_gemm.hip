@@ -20,10 +20,12 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kStepBytes = 64;               // bytes of depth per row per main-loop step
 constexpr int kChunks = kStepBytes / 16;     // 16-byte chunks per row per step
 constexpr uint32_t kLowNibbles = 0x0F0F0F0Fu;
+constexpr int kStages = 3;                   // depth steps resident in LDS
 
 enum LoadMode {
     kDenseAligned = 0,  // rows 16-byte aligned, ceil(K/2) a multiple of 16
@@ -40,6 +42,7 @@ struct KernelArgs {
     const int32_t *colsumB;
     int M, N, K;
     int kbytes;  // ceil(K/2)
+    uint32_t a_bytes, b_bytes;  // extent of A and B for range-checked loads (aligned modes)
     long lda, ldb, ldc;
     int za, zb;
     int tiles_m, tiles_n;
@@ -71,20 +74,17 @@ __device__ __forceinline__ uint32_t load_dword_guarded(const uint8_t *row, long 
     return v;
 }
 
-// One 16-byte chunk of a dense packed row: bytes [kb, kb+16) of the row, zero past the end.
-template <bool ALIGNED>
-__device__ __forceinline__ uint4 load_dense_chunk(const uint8_t *row, int kb, int kbytes, bool odd_k)
+__device__ __forceinline__ v4u as_v4u(const uint4 &x) { return v4u{x.x, x.y, x.z, x.w}; }
+
+// One 16-byte chunk of a dense packed row of any alignment: bytes [kb, kb+16), zero past the end.
+__device__ __forceinline__ uint4 load_dense_chunk_generic(const uint8_t *row, int kb, int kbytes, bool odd_k)
 {
     uint4 v = make_uint4(0, 0, 0, 0);
-    if constexpr (ALIGNED) {
-        if (kb < kbytes) v = *reinterpret_cast<const uint4 *>(row + kb);
-    } else {
-        if (kb < kbytes) {
-            v.x = load_dword_guarded(row, kb, kbytes, odd_k);
-            v.y = load_dword_guarded(row, kb + 4, kbytes, odd_k);
-            v.z = load_dword_guarded(row, kb + 8, kbytes, odd_k);
-            v.w = load_dword_guarded(row, kb + 12, kbytes, odd_k);
-        }
+    if (kb < kbytes) {
+        v.x = load_dword_guarded(row, kb, kbytes, odd_k);
+        v.y = load_dword_guarded(row, kb + 4, kbytes, odd_k);
+        v.z = load_dword_guarded(row, kb + 8, kbytes, odd_k);
+        v.w = load_dword_guarded(row, kb + 12, kbytes, odd_k);
     }
     return v;
 }
@@ -162,25 +162,17 @@ __device__ __forceinline__ uint32_t load_conv_dword_generic(const uint8_t *x, co
     return v;
 }
 
-__device__ __forceinline__ v4i low_codes(const uint4 &p)
+// Workgroup barrier that waits for this wave's LDS traffic only: global loads issued for
+// later steps stay in flight across it (a full fence would drain them at every step).
+__device__ __forceinline__ void block_barrier()
 {
-    v4i r;
-    r[0] = p.x & kLowNibbles;
-    r[1] = p.y & kLowNibbles;
-    r[2] = p.z & kLowNibbles;
-    r[3] = p.w & kLowNibbles;
-    return r;
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-__device__ __forceinline__ v4i high_codes(const uint4 &p)
-{
-    v4i r;
-    r[0] = (p.x >> 4) & kLowNibbles;
-    r[1] = (p.y >> 4) & kLowNibbles;
-    r[2] = (p.z >> 4) & kLowNibbles;
-    r[3] = (p.w >> 4) & kLowNibbles;
-    return r;
-}
+// The widening step: even depth positions (low nibbles) and odd ones (high nibbles) of
+// four packed dwords, each as sixteen int8 lanes for the matrix cores.
+__device__ __forceinline__ v4i low_codes(const v4u &p) { return (v4i)(p & kLowNibbles); }
+__device__ __forceinline__ v4i high_codes(const v4u &p) { return (v4i)((p >> 4) & kLowNibbles); }
 
 // Workgroup id -> output tile.  Consecutive workgroup ids land on different XCDs (each with
 // its own L2), so ids are first regrouped so that one XCD owns a contiguous run of tiles,
@@ -201,8 +193,22 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
     tn = in_band / band_rows;
 }
 
+// Waves per SIMD the register budget must allow: wave tiles of up to 128 x 64 (128 accumulator
+// registers) fit two waves per SIMD, so that two workgroups share a compute unit and one's
+// epilogue overlaps the other's main loop.
+constexpr int min_waves_per_simd(int wm, int wn) { return (wm * wn <= 128 * 64) ? 2 : 1; }
+
+// Raw buffer descriptor over [base, base + bytes): loads past the end return zero, which
+// gives the zero fill of the depth tail without a branch.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, static_cast<int>(bytes), 0x00020000);
+}
+
+constexpr uint32_t kOutOfRange = 0xFFFFFFF0u;  // a buffer offset that always fails the range check
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE>
-__global__ void __launch_bounds__(WAVES_M *WAVES_N * 64)
+__global__ void __launch_bounds__(WAVES_M *WAVES_N * 64, (min_waves_per_simd(BM / WAVES_M, BN / WAVES_N)))
 q4_gemm_kernel(const KernelArgs p)
 {
     constexpr int T = WAVES_M * WAVES_N * 64;
@@ -214,7 +220,7 @@ q4_gemm_kernel(const KernelArgs p)
     constexpr bool kConv = (MODE == kConvAligned || MODE == kConvGeneric);
     constexpr bool kAligned = (MODE == kDenseAligned || MODE == kConvAligned);
 
-    __shared__ uint4 lds[2][(BM + BN) * kChunks];
+    __shared__ uint4 lds[kStages][(BM + BN) * kChunks];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -226,56 +232,75 @@ q4_gemm_kernel(const KernelArgs p)
     const int m0 = tm * BM, n0 = tn * BN;
     const bool odd_k = (p.K & 1) != 0;
 
-    // ---- what this thread copies from HBM to LDS at every step
+    // ---- what this thread copies from HBM to LDS at every step: NA chunks of A, NB of B.
+    // Rows past M (or N) repeat the last valid row; their products are never stored.
     const int chunk = tid % kChunks;  // same for all of a thread's slots (T is a multiple of kChunks)
+    const int chunk_limit = p.kbytes - chunk * 16;  // this thread's chunk of step kt exists iff kt * 64 < chunk_limit
     const uint8_t *a_row[NA];
+    uint32_t a_off[NA];
     PatchOrigin a_org[NA];
     int a_lds[NA];
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
         const int row = (tid + i * T) / kChunks;
-        const long m = min(static_cast<long>(m0 + row), static_cast<long>(p.M - 1));  // rows past M repeat the last one; never stored
+        const long m = min(static_cast<long>(m0 + row), static_cast<long>(p.M - 1));
         if constexpr (kConv) a_org[i] = patch_origin(p.g, m);
+        else if constexpr (kAligned) a_off[i] = static_cast<uint32_t>(m * p.lda + chunk * 16);
         else a_row[i] = p.A + m * p.lda;
         a_lds[i] = row * kChunks + (chunk ^ swizzle(row));
     }
     const uint8_t *b_row[NB];
+    uint32_t b_off[NB];
     int b_lds[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int row = (tid + i * T) / kChunks;
         const long n = min(static_cast<long>(n0 + row), static_cast<long>(p.N - 1));
-        b_row[i] = p.B + n * p.ldb;
+        if constexpr (kAligned) b_off[i] = static_cast<uint32_t>(n * p.ldb + chunk * 16);
+        else b_row[i] = p.B + n * p.ldb;
         b_lds[i] = BM * kChunks + row * kChunks + (chunk ^ swizzle(row));
     }
+    __amdgpu_buffer_rsrc_t a_rsrc, b_rsrc;
+    if constexpr (MODE == kDenseAligned) a_rsrc = make_rsrc(p.A, p.a_bytes);
+    if constexpr (kAligned) b_rsrc = make_rsrc(p.B, p.b_bytes);
 
-    uint4 a_reg[NA], b_reg[NB];
+    v4u a_reg[NA], b_reg[NB];
     auto fetch = [&](int kt) {
-        const int kb = kt * kStepBytes + chunk * 16;
+        const int k0 = kt * kStepBytes;
+        const int kb = k0 + chunk * 16;
+        const bool present = k0 < chunk_limit;
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            if constexpr (MODE == kConvAligned) {
-                a_reg[i] = load_conv_chunk_aligned(p.A, p.g, a_org[i], kb, p.kbytes);
+            if constexpr (MODE == kDenseAligned) {
+                a_reg[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, present ? a_off[i] : kOutOfRange, k0, 0);
+            } else if constexpr (MODE == kConvAligned) {
+                a_reg[i] = as_v4u(load_conv_chunk_aligned(p.A, p.g, a_org[i], kb, p.kbytes));
             } else if constexpr (MODE == kConvGeneric) {
-                a_reg[i] = make_uint4(0, 0, 0, 0);
+                a_reg[i] = v4u{0, 0, 0, 0};
                 if (kb < p.kbytes) {
-                    a_reg[i].x = load_conv_dword_generic(p.A, p.g, a_org[i], 2 * kb, p.K);
-                    a_reg[i].y = load_conv_dword_generic(p.A, p.g, a_org[i], 2 * kb + 8, p.K);
-                    a_reg[i].z = load_conv_dword_generic(p.A, p.g, a_org[i], 2 * kb + 16, p.K);
-                    a_reg[i].w = load_conv_dword_generic(p.A, p.g, a_org[i], 2 * kb + 24, p.K);
+                    a_reg[i][0] = load_conv_dword_generic(p.A, p.g, a_org[i], 2 * kb, p.K);
+                    a_reg[i][1] = load_conv_dword_generic(p.A, p.g, a_org[i], 2 * kb + 8, p.K);
+                    a_reg[i][2] = load_conv_dword_generic(p.A, p.g, a_org[i], 2 * kb + 16, p.K);
+                    a_reg[i][3] = load_conv_dword_generic(p.A, p.g, a_org[i], 2 * kb + 24, p.K);
                 }
             } else {
-                a_reg[i] = load_dense_chunk<kAligned>(a_row[i], kb, p.kbytes, odd_k);
+                a_reg[i] = as_v4u(load_dense_chunk_generic(a_row[i], kb, p.kbytes, odd_k));
             }
         }
 #pragma unroll
-        for (int i = 0; i < NB; ++i) b_reg[i] = load_dense_chunk<kAligned>(b_row[i], kb, p.kbytes, odd_k);
+        for (int i = 0; i < NB; ++i) {
+            if constexpr (kAligned)
+                b_reg[i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, present ? b_off[i] : kOutOfRange, k0, 0);
+            else
+                b_reg[i] = as_v4u(load_dense_chunk_generic(b_row[i], kb, p.kbytes, odd_k));
+        }
     };
     auto stash = [&](int buf) {
+        v4u *dst = reinterpret_cast<v4u *>(lds[buf]);
 #pragma unroll
-        for (int i = 0; i < NA; ++i) lds[buf][a_lds[i]] = a_reg[i];
+        for (int i = 0; i < NA; ++i) dst[a_lds[i]] = a_reg[i];
 #pragma unroll
-        for (int i = 0; i < NB; ++i) lds[buf][b_lds[i]] = b_reg[i];
+        for (int i = 0; i < NB; ++i) dst[b_lds[i]] = b_reg[i];
     };
 
     // ---- what this lane reads back for the matrix cores: row (lane % 32) of each 32-row
@@ -299,42 +324,64 @@ q4_gemm_kernel(const KernelArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
+    // ---- main loop.  LDS holds a ring of three depth steps, so that the step being written
+    // (kt + 2) is never one that some wave may still read (kt, and kt + 1 whose first half is
+    // pre-read); one barrier per step publishes the write.  HBM data for step kt + 3 is in
+    // flight in registers while step kt is multiplied, and the packed fragments of the next
+    // half-step are read from LDS while the matrix cores work on the current one.
     const int steps = (p.kbytes + kStepBytes - 1) / kStepBytes;
     fetch(0);
     stash(0);
-    __syncthreads();
+    fetch(1);
+    stash(1);
+    fetch(2);
+    block_barrier();
 
-    for (int kt = 0; kt < steps; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < steps) fetch(kt + 1);
+    v4u pa[2][FM], pb[2][FN];
+    auto read_frags = [&](int buf, int s, int slot) {
+        const v4u *src = reinterpret_cast<const v4u *>(lds[buf]);
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            uint4 pa[FM], pb[FN];
+        for (int i = 0; i < FM; ++i) pa[slot][i] = src[a_frag[s] + i * 32 * kChunks];
 #pragma unroll
-            for (int i = 0; i < FM; ++i) pa[i] = lds[buf][a_frag[s] + i * 32 * kChunks];
+        for (int j = 0; j < FN; ++j) pb[slot][j] = src[b_frag[s] + j * 32 * kChunks];
+    };
+    auto multiply = [&](int slot) {
+        v4i blo[FN], bhi[FN];
 #pragma unroll
-            for (int j = 0; j < FN; ++j) pb[j] = lds[buf][b_frag[s] + j * 32 * kChunks];
-            v4i alo[FM], ahi[FM], blo[FN], bhi[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                alo[i] = low_codes(pa[i]);
-                ahi[i] = high_codes(pa[i]);
-            }
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                blo[j] = low_codes(pb[j]);
-                bhi[j] = high_codes(pb[j]);
-            }
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i], blo[j], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi[i], bhi[j], acc[i][j], 0, 0, 0);
-                }
+        for (int j = 0; j < FN; ++j) {
+            blo[j] = low_codes(pb[slot][j]);
+            bhi[j] = high_codes(pb[slot][j]);
         }
-        if (kt + 1 < steps) stash(buf ^ 1);
-        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const v4i alo = low_codes(pa[slot][i]);
+            const v4i ahi = high_codes(pa[slot][i]);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo, blo[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi, bhi[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    read_frags(0, 0, 0);
+    int cur = 0;  // kt % 3
+    for (int kt = 0; kt < steps; ++kt) {
+        const int nxt = (cur == kStages - 1) ? 0 : cur + 1;
+        const int nxt2 = (nxt == kStages - 1) ? 0 : nxt + 1;
+        // Past the last step the loaders return zeros and the ring slots written or pre-read are
+        // ones nobody uses any more, so nothing below needs a branch.
+        stash(nxt2);
+        fetch(kt + 3);
+        read_frags(cur, 1, 1);
+        __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads ahead of the products they overlap with
+        multiply(0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(nxt, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(1);
+        __builtin_amdgcn_sched_barrier(0);
+        block_barrier();
+        cur = nxt;
     }
 
     // ---- epilogue: zero-point terms of Eq. (2), then store.  In a 32x32 accumulator
@@ -356,6 +403,175 @@ q4_gemm_kernel(const KernelArgs p)
         }
     }
 }
+
+// ---------------------------------------------------------------------------------------
+// Fast path for dense, 16-byte aligned operands.  Same tiling and the same LDS layout as
+// q4_gemm_kernel, but the packed tiles go from HBM straight into LDS (buffer_load ... lds):
+// no staging registers and no LDS store instructions in the wave's instruction stream, and
+// a ring of STAGES depth steps whose loads stay in flight across the per-step barrier.
+// A wave-wide load fills 64 consecutive 16-byte LDS slots (16 rows x 4 chunks); the XOR
+// swizzle is applied by choosing which chunk of global memory each lane fetches.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+__global__ void __launch_bounds__(WAVES_M *WAVES_N * 64, (min_waves_per_simd(BM / WAVES_M, BN / WAVES_N)))
+q4_gemm_direct_kernel(const KernelArgs p)
+{
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int GA = BM / 16 / NW, GB = BN / 16 / NW;  // 16-row groups per wave
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 fragments");
+    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "tile rows must divide over the waves");
+    static_assert(STAGES == 3 || STAGES == 4, "ring depth");
+    constexpr int kLoadsPerStep = GA + GB;
+    constexpr int kStageSlots = (BM + BN) * kChunks;
+
+    __shared__ uint4 lds[STAGES][kStageSlots];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    // ---- HBM -> LDS: this lane's share of each 16-row group
+    const int lrow = lane >> 2;    // row inside the group
+    const int pchunk = lane & 3;   // physical chunk it fills
+    uint32_t a_off[GA], b_off[GB];
+    int a_lim[GA], b_lim[GB];      // the lane's chunk of step kt exists iff kt * 64 < limit
+#pragma unroll
+    for (int i = 0; i < GA; ++i) {
+        const int row = (wave + i * NW) * 16 + lrow;
+        const int c = pchunk ^ swizzle(row);
+        const long m = min(static_cast<long>(m0 + row), static_cast<long>(p.M - 1));
+        a_off[i] = static_cast<uint32_t>(m * p.lda + c * 16);
+        a_lim[i] = p.kbytes - c * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < GB; ++i) {
+        const int row = (wave + i * NW) * 16 + lrow;
+        const int c = pchunk ^ swizzle(row);
+        const long n = min(static_cast<long>(n0 + row), static_cast<long>(p.N - 1));
+        b_off[i] = static_cast<uint32_t>(n * p.ldb + c * 16);
+        b_lim[i] = p.kbytes - c * 16;
+    }
+    const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(p.A, p.a_bytes);
+    const __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(p.B, p.b_bytes);
+
+    typedef __attribute__((address_space(3))) void *lds_ptr;
+    auto issue = [&](int kt, int slot) {
+        const int k0 = kt * kStepBytes;
+#pragma unroll
+        for (int i = 0; i < GA; ++i) {
+            uint4 *dst = &lds[slot][(wave + i * NW) * 16 * kChunks];
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr)dst, 16, k0 < a_lim[i] ? a_off[i] : kOutOfRange, k0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < GB; ++i) {
+            uint4 *dst = &lds[slot][BM * kChunks + (wave + i * NW) * 16 * kChunks];
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr)dst, 16, k0 < b_lim[i] ? b_off[i] : kOutOfRange, k0, 0, 0);
+        }
+    };
+
+    // ---- LDS -> matrix cores: row (lane % 32) of each fragment, chunk 2*s + lane/32
+    const int frow = lane & 31;
+    const int half = lane >> 5;
+    const int fsw = swizzle(frow);
+    int a_frag[2], b_frag[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int c = (2 * s + half) ^ fsw;
+        a_frag[s] = (wm * WM + frow) * kChunks + c;
+        b_frag[s] = BM * kChunks + (wn * WN + frow) * kChunks + c;
+    }
+
+    v16i acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    v4u pa[2][FM], pb[2][FN];
+    auto read_frags = [&](int slot, int s, int reg) {
+        const v4u *src = reinterpret_cast<const v4u *>(lds[slot]);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) pa[reg][i] = src[a_frag[s] + i * 32 * kChunks];
+#pragma unroll
+        for (int j = 0; j < FN; ++j) pb[reg][j] = src[b_frag[s] + j * 32 * kChunks];
+    };
+    auto multiply = [&](int reg) {
+        v4i blo[FN], bhi[FN];
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            blo[j] = low_codes(pb[reg][j]);
+            bhi[j] = high_codes(pb[reg][j]);
+        }
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const v4i alo = low_codes(pa[reg][i]);
+            const v4i ahi = high_codes(pa[reg][i]);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo, blo[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi, bhi[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    // Step kt lives in ring slot kt % STAGES.  Iteration kt issues the loads of step
+    // kt + STAGES - 1 into the slot that was last read in iteration kt - 1, multiplies step kt
+    // and pre-reads the first half of step kt + 1.  The wait before the barrier lets the
+    // newest STAGES - 3 steps stay in flight; everything older has landed and is published.
+    const int steps = (p.kbytes + kStepBytes - 1) / kStepBytes;
+#pragma unroll
+    for (int t = 0; t < STAGES - 1; ++t) issue(t, t);
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    read_frags(0, 0, 0);
+    int cur = 0;
+    for (int kt = 0; kt < steps; ++kt) {
+        const int nxt = (cur == STAGES - 1) ? 0 : cur + 1;
+        const int last = (cur == 0) ? STAGES - 1 : cur - 1;
+        issue(kt + STAGES - 1, last);
+        read_frags(cur, 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(nxt, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(1);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((STAGES - 3) * kLoadsPerStep) : "memory");
+        cur = nxt;
+    }
+
+    // ---- epilogue: zero-point terms of Eq. (2), then store.  In a 32x32 accumulator
+    // fragment register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+    const int kzz = p.K * p.za * p.zb;
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        const int n = n0 + wn * WN + j * 32 + frow;
+        if (n >= p.N) continue;
+        const int col_term = kzz - p.za * p.colsumB[n];
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * WM + i * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                if (m < p.M)
+                    p.C[m * p.ldc + n] = acc[i][j][v] + col_term - p.zb * p.rowsumA[m];
+            }
+        }
+    }
+#endif
+}
+
+// Ring depth of the direct kernel: four steps when one workgroup per compute unit owns the
+// LDS anyway (eight waves), three when two workgroups must share its 160 KB.
+constexpr int direct_stages(int bm, int bn, int waves) { return (waves >= 8 && (bm + bn) * 64 * 4 <= 160 * 1024) ? 4 : 3; }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 hipError_t launch_tile(const GemmProblem &q, hipStream_t stream)
@@ -381,11 +597,18 @@ hipError_t launch_tile(const GemmProblem &q, hipStream_t stream)
     const dim3 grid(static_cast<unsigned>(a.tiles_m) * static_cast<unsigned>(a.tiles_n));
     const dim3 block(WAVES_M * WAVES_N * 64);
 
-    const bool b_aligned = (reinterpret_cast<uintptr_t>(q.B) % 16 == 0) && (q.ldb % 16 == 0) && (a.kbytes % 16 == 0) && (q.K % 2 == 0);
+    // Range-checked 16-byte loads need aligned rows, whole chunks and extents below 4 GiB.
+    constexpr long kMaxExtent = 0xFFFFFF00L;
+    const long b_extent = (q.N - 1L) * q.ldb + a.kbytes;
+    const long a_extent = q.is_conv ? 0 : (q.M - 1L) * q.lda + a.kbytes;
+    a.a_bytes = static_cast<uint32_t>(a_extent < kMaxExtent ? a_extent : 0);
+    a.b_bytes = static_cast<uint32_t>(b_extent < kMaxExtent ? b_extent : 0);
+    const bool b_aligned = (reinterpret_cast<uintptr_t>(q.B) % 16 == 0) && (q.ldb % 16 == 0) && (a.kbytes % 16 == 0) &&
+                           (q.K % 2 == 0) && b_extent < kMaxExtent;
     if (!q.is_conv) {
-        const bool a_aligned = (reinterpret_cast<uintptr_t>(q.A) % 16 == 0) && (q.lda % 16 == 0);
+        const bool a_aligned = (reinterpret_cast<uintptr_t>(q.A) % 16 == 0) && (q.lda % 16 == 0) && a_extent < kMaxExtent;
         if (a_aligned && b_aligned)
-            q4_gemm_kernel<BM, BN, WAVES_M, WAVES_N, kDenseAligned><<<grid, block, 0, stream>>>(a);
+            q4_gemm_direct_kernel<BM, BN, WAVES_M, WAVES_N, direct_stages(BM, BN, WAVES_M * WAVES_N)><<<grid, block, 0, stream>>>(a);
         else
             q4_gemm_kernel<BM, BN, WAVES_M, WAVES_N, kDenseGeneric><<<grid, block, 0, stream>>>(a);
     } else {
@@ -414,6 +637,9 @@ hipError_t launch_gemm(const GemmProblem &p, int force_tile, hipStream_t stream)
     switch (tile) {
     case 0: return launch_tile<256, 256, 2, 4>(p, stream);
     case 1: return launch_tile<128, 128, 2, 2>(p, stream);
+    case 3: return launch_tile<256, 128, 2, 2>(p, stream);
+    case 4: return launch_tile<128, 256, 2, 2>(p, stream);
+    case 5: return launch_tile<256, 256, 2, 2>(p, stream);
     default: return launch_tile<64, 64, 2, 2>(p, stream);
     }
 }
