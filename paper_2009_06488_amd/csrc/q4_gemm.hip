@@ -496,55 +496,78 @@ q4_gemm_direct_kernel(const KernelArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    v4u pa[2][FM], pb[2][FN];
-    auto read_frags = [&](int slot, int s, int reg) {
-        const v4u *src = reinterpret_cast<const v4u *>(lds[slot]);
-#pragma unroll
-        for (int i = 0; i < FM; ++i) pa[reg][i] = src[a_frag[s] + i * 32 * kChunks];
-#pragma unroll
-        for (int j = 0; j < FN; ++j) pb[reg][j] = src[b_frag[s] + j * 32 * kChunks];
+    // ---- software pipeline.  A depth step is multiplied in two half-steps of 64 codes.
+    // Registers hold two sets of packed fragments (one per half-step parity).  While the matrix
+    // cores work through the FM x FN fragment products of half-step (kt, h), the same wave
+    //   (a) widens A fragment i+1 during the products of fragment row i, and the B fragments
+    //       of the following half-step spread over all rows;
+    //   (b) refills every packed register as soon as it has been widened, with the fragment of
+    //       half-step (kt+1, h) -- so each LDS read has a whole half-step to land;
+    //   (c) in the first half-step issues the HBM -> LDS loads of step kt + STAGES into the
+    //       ring slot of step kt, whose fragments were all read during iteration kt - 1.
+    // None of this depends on the products in flight, so it fills the issue slots between them.
+    v4u pa[2][FM], pb[2][FN];        // packed fragments, by half-step parity
+    v4i ub_lo[2][FN], ub_hi[2][FN];  // widened B fragments, by half-step parity
+    v4i ua_lo, ua_hi;                // widened A fragment for the next fragment row
+    auto read_a = [&](int slot, int s, int set, int i) {
+        pa[set][i] = reinterpret_cast<const v4u *>(lds[slot])[a_frag[s] + i * 32 * kChunks];
     };
-    auto multiply = [&](int reg) {
-        v4i blo[FN], bhi[FN];
+    auto read_b = [&](int slot, int s, int set) {
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            blo[j] = low_codes(pb[reg][j]);
-            bhi[j] = high_codes(pb[reg][j]);
+        for (int j = 0; j < FN; ++j) pb[set][j] = reinterpret_cast<const v4u *>(lds[slot])[b_frag[s] + j * 32 * kChunks];
+    };
+    auto widen_b = [&](int set, int first, int last) {  // dwords [first, last) of the set's B fragments
+#pragma unroll
+        for (int d = 0; d < 4 * FN; ++d) {
+            if (d < first || d >= last) continue;
+            const uint32_t w = pb[set][d / 4][d % 4];
+            ub_lo[set][d / 4][d % 4] = static_cast<int>(w & kLowNibbles);
+            ub_hi[set][d / 4][d % 4] = static_cast<int>((w >> 4) & kLowNibbles);
         }
+    };
+    auto half_step = [&](const int set, const int slot_next) {
+        const int other = set ^ 1;
+        read_b(slot_next, set, set);  // this parity's B was widened during the previous half-step
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
-            const v4i alo = low_codes(pa[reg][i]);
-            const v4i ahi = high_codes(pa[reg][i]);
+            const v4i alo = ua_lo, ahi = ua_hi;
 #pragma unroll
-            for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo, blo[j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo, ub_lo[set][j], acc[i][j], 0, 0, 0);
 #pragma unroll
-            for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi, bhi[j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi, ub_hi[set][j], acc[i][j], 0, 0, 0);
+            const v4u next_a = (i + 1 < FM) ? pa[set][(i + 1) % FM] : pa[other][0];
+            ua_lo = low_codes(next_a);
+            ua_hi = high_codes(next_a);
+            widen_b(other, i * 4 * FN / FM, (i + 1) * 4 * FN / FM);
+            read_a(slot_next, set, set, i);  // fragment i of this set was widened one row ago
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // Step kt lives in ring slot kt % STAGES.  Iteration kt issues the loads of step
-    // kt + STAGES - 1 into the slot that was last read in iteration kt - 1, multiplies step kt
-    // and pre-reads the first half of step kt + 1.  The wait before the barrier lets the
-    // newest STAGES - 3 steps stay in flight; everything older has landed and is published.
+    // Step kt lives in ring slot kt % STAGES.  The wait before each barrier lets the newest
+    // STAGES - 2 steps stay in flight; step kt + 2, read during iteration kt + 1, has landed.
     const int steps = (p.kbytes + kStepBytes - 1) / kStepBytes;
 #pragma unroll
-    for (int t = 0; t < STAGES - 1; ++t) issue(t, t);
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    read_frags(0, 0, 0);
+    for (int t = 0; t < STAGES; ++t) issue(t, t);
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((STAGES - 2) * kLoadsPerStep) : "memory");
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        read_b(0, h, h);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) read_a(0, h, h, i);
+    }
+    widen_b(0, 0, 4 * FN);
+    ua_lo = low_codes(pa[0][0]);
+    ua_hi = high_codes(pa[0][0]);
+    block_barrier();  // every wave has taken step 0 out of its slot before the loop refills it
     int cur = 0;
     for (int kt = 0; kt < steps; ++kt) {
         const int nxt = (cur == STAGES - 1) ? 0 : cur + 1;
-        const int last = (cur == 0) ? STAGES - 1 : cur - 1;
-        issue(kt + STAGES - 1, last);
-        read_frags(cur, 1, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(0);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(nxt, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(1);
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((STAGES - 3) * kLoadsPerStep) : "memory");
+        issue(kt + STAGES, cur);
+        half_step(0, nxt);
+        half_step(1, nxt);
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((STAGES - 2) * kLoadsPerStep) : "memory");
         cur = nxt;
     }
 
