@@ -12,6 +12,8 @@
 // packed dword w gives (w & 0x0F0F0F0F) and ((w >> 4) & 0x0F0F0F0F).  These hold the even
 // and the odd depth positions; since A and B are split the same way and a dot product does
 // not depend on the order of its terms, no re-interleave is needed.
+#include <stdlib.h>
+
 #include "q4_kernels.h"
 
 namespace q4 {
@@ -46,6 +48,8 @@ struct KernelArgs {
     long lda, ldb, ldc;
     int za, zb;
     int tiles_m, tiles_n;
+    int stagger_first, stagger_count;  // workgroups [first, first + count) start late by stagger_ticks
+    int stagger_ticks;                 // in ticks of the 100 MHz wall clock
     ConvGeom g;
 };
 
@@ -162,6 +166,20 @@ __device__ __forceinline__ uint32_t load_conv_dword_generic(const uint8_t *x, co
     return v;
 }
 
+// Two workgroups that share a compute unit and start together reach their epilogues together,
+// and then nothing hides the burst of C stores.  Holding back the second workgroup of each
+// compute unit once, at the start, breaks that symmetry: from then on one workgroup's stores
+// overlap the other's products.  The wait is bounded by the clock and by an iteration cap.
+__device__ __forceinline__ void stagger_start(const KernelArgs &p)
+{
+    const int b = static_cast<int>(blockIdx.x) - p.stagger_first;
+    if (p.stagger_ticks > 0 && b >= 0 && b < p.stagger_count) {
+        const unsigned long long t0 = wall_clock64();
+        for (int spin = 0; spin < (1 << 16) && wall_clock64() - t0 < static_cast<unsigned long long>(p.stagger_ticks); ++spin)
+            __builtin_amdgcn_s_sleep(32);
+    }
+}
+
 // Workgroup barrier that waits for this wave's LDS traffic only: global loads issued for
 // later steps stay in flight across it (a full fence would drain them at every step).
 __device__ __forceinline__ void block_barrier()
@@ -193,6 +211,46 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
     tn = in_band / band_rows;
 }
 
+// ---- epilogue shared by both kernels.  The zero-point terms of Eq. (2) are staged in LDS
+// once per tile, before the main loop: row_term[r] = -zb * rowsumA[m0 + r] and
+// col_term[c] = K * za * zb - za * colsumB[n0 + c], so that C = raw + row_term + col_term.
+template <int BM, int BN, int T>
+__device__ __forceinline__ void stage_terms(int *terms, const KernelArgs &p, int m0, int n0, int tid)
+{
+    for (int r = tid; r < BM; r += T) terms[r] = (m0 + r < p.M) ? -p.zb * p.rowsumA[m0 + r] : 0;
+    const int kzz = p.K * p.za * p.zb;
+    for (int c = tid; c < BN; c += T) terms[BM + c] = (n0 + c < p.N) ? kzz - p.za * p.colsumB[n0 + c] : 0;
+}
+
+// In a 32x32 accumulator fragment register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4 and
+// column l%32: a half-wave stores 128 contiguous bytes of one row of C per instruction.
+template <int BM, int FM, int FN>
+__device__ __forceinline__ void store_tile(const v16i (&acc)[FM][FN], const int *terms, const KernelArgs &p,
+                                           int m_wave, int n_wave, int row_wave, int col_wave, int lane)
+{
+    const int frow = lane & 31, half = lane >> 5;
+    const bool interior = (m_wave + FM * 32 <= p.M) && (n_wave + FN * 32 <= p.N);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        const int n = n_wave + j * 32 + frow;
+        const int col_term = terms[BM + col_wave + j * 32 + frow];
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int r = i * 32 + 8 * q + 4 * half;
+                const v4i row_term = *reinterpret_cast<const v4i *>(&terms[row_wave + r]);
+                int32_t *dst = p.C + static_cast<long>(m_wave + r) * p.ldc + n;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int value = acc[i][j][4 * q + e] + col_term + row_term[e];
+                    if (interior || (m_wave + r + e < p.M && n < p.N)) dst[e * p.ldc] = value;
+                }
+            }
+        }
+    }
+}
+
 // Waves per SIMD the register budget must allow: wave tiles of up to 128 x 64 (128 accumulator
 // registers) fit two waves per SIMD, so that two workgroups share a compute unit and one's
 // epilogue overlaps the other's main loop.
@@ -221,6 +279,7 @@ q4_gemm_kernel(const KernelArgs p)
     constexpr bool kAligned = (MODE == kDenseAligned || MODE == kConvAligned);
 
     __shared__ uint4 lds[kStages][(BM + BN) * kChunks];
+    __shared__ __attribute__((aligned(16))) int terms[BM + BN];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -231,6 +290,7 @@ q4_gemm_kernel(const KernelArgs p)
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const bool odd_k = (p.K & 1) != 0;
+    stage_terms<BM, BN, T>(terms, p, m0, n0, tid);  // published by the barriers of the main loop
 
     // ---- what this thread copies from HBM to LDS at every step: NA chunks of A, NB of B.
     // Rows past M (or N) repeat the last valid row; their products are never stored.
@@ -384,24 +444,9 @@ q4_gemm_kernel(const KernelArgs p)
         cur = nxt;
     }
 
-    // ---- epilogue: zero-point terms of Eq. (2), then store.  In a 32x32 accumulator
-    // fragment register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
-    const int kzz = p.K * p.za * p.zb;
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-        const int n = n0 + wn * WN + j * 32 + frow;
-        if (n >= p.N) continue;
-        const int col_term = kzz - p.za * p.colsumB[n];
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * WM + i * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                if (m < p.M)
-                    p.C[m * p.ldc + n] = acc[i][j][v] + col_term - p.zb * p.rowsumA[m];
-            }
-        }
-    }
+    // ---- epilogue: add the zero-point terms of Eq. (2) and store
+    store_tile<BM, FM, FN>(acc, terms, p, m0 + wm * WM, n0 + wn * WN, wm * WM, wn * WN, lane);
+
 }
 
 // ---------------------------------------------------------------------------------------
@@ -427,6 +472,7 @@ q4_gemm_direct_kernel(const KernelArgs p)
     constexpr int kStageSlots = (BM + BN) * kChunks;
 
     __shared__ uint4 lds[STAGES][kStageSlots];
+    __shared__ __attribute__((aligned(16))) int terms[BM + BN];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -435,7 +481,9 @@ q4_gemm_direct_kernel(const KernelArgs p)
 
     int tm, tn;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    stagger_start(p);
     const int m0 = tm * BM, n0 = tn * BN;
+    stage_terms<BM, BN, NW * 64>(terms, p, m0, n0, tid);  // published by the barriers of the main loop
 
     // ---- HBM -> LDS: this lane's share of each 16-row group
     const int lrow = lane >> 2;    // row inside the group
@@ -571,24 +619,8 @@ q4_gemm_direct_kernel(const KernelArgs p)
         cur = nxt;
     }
 
-    // ---- epilogue: zero-point terms of Eq. (2), then store.  In a 32x32 accumulator
-    // fragment register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
-    const int kzz = p.K * p.za * p.zb;
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-        const int n = n0 + wn * WN + j * 32 + frow;
-        if (n >= p.N) continue;
-        const int col_term = kzz - p.za * p.colsumB[n];
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * WM + i * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                if (m < p.M)
-                    p.C[m * p.ldc + n] = acc[i][j][v] + col_term - p.zb * p.rowsumA[m];
-            }
-        }
-    }
+    // ---- epilogue: add the zero-point terms of Eq. (2) and store
+    store_tile<BM, FM, FN>(acc, terms, p, m0 + wm * WM, n0 + wn * WN, wm * WM, wn * WN, lane);
 #endif
 }
 
@@ -617,6 +649,20 @@ hipError_t launch_tile(const GemmProblem &q, hipStream_t stream)
     a.tiles_m = (q.M + BM - 1) / BM;
     a.tiles_n = (q.N + BN - 1) / BN;
     a.g = q.g;
+    // Stagger only when two workgroups share a compute unit and there are several rounds of tiles.
+    constexpr int kComputeUnits = 256;
+    constexpr bool kTwoPerCu = min_waves_per_simd(BM / WAVES_M, BN / WAVES_N) == 2 && WAVES_M * WAVES_N == 4;
+    const long n_tiles = static_cast<long>(a.tiles_m) * a.tiles_n;
+    a.stagger_first = kComputeUnits;
+    a.stagger_count = kComputeUnits;
+    a.stagger_ticks = 0;
+    if (kTwoPerCu && n_tiles >= 4 * kComputeUnits) {
+        // about a third of the time one workgroup alone needs for a tile (12 TOP/s per compute unit)
+        const double tile_us = 2.0 * BM * BN * static_cast<double>(q.K) / 12.0e6;
+        const char *e = getenv("Q4_STAGGER_PCT");
+        const double pct = e ? atof(e) : 35.0;
+        a.stagger_ticks = static_cast<int>(tile_us * pct);  // 100 ticks per microsecond, pct / 100
+    }
     const dim3 grid(static_cast<unsigned>(a.tiles_m) * static_cast<unsigned>(a.tiles_n));
     const dim3 block(WAVES_M * WAVES_N * 64);
 
