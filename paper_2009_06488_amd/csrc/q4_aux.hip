@@ -134,6 +134,51 @@ repack_kn_to_nk_kernel(const uint8_t *__restrict__ src, int K, int N, long ld_sr
     drain_transposed(tile, k0, n0, K, N, dst, ld_dst);
 }
 
+
+// Fast path of the packed transpose: 128 (k) x 128 (n) codes per block, everything in 16-byte
+// pieces.  A thread takes two consecutive k rows and 32 columns; from a pair of packed dwords
+// X (row k) and Y (row k+1) it forms the output bytes code(k, n) | code(k+1, n) << 4 for the even
+// columns, (X & 0x0F0F0F0F) | ((Y << 4) & 0xF0F0F0F0), and for the odd ones,
+// ((X >> 4) & 0x0F0F0F0F) | (Y & 0xF0F0F0F0).  Those bytes are scattered into an LDS tile laid
+// out as the destination (one row per n) and drained with 16-byte stores.
+constexpr int kRT = 128;
+__global__ void __launch_bounds__(256)
+repack_kn_to_nk_fast_kernel(const uint8_t *__restrict__ src, int K, int N, long ld_src,
+                            uint8_t *__restrict__ dst, long ld_dst)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t out[kRT][kRT / 2 + 16];
+    const int k0 = blockIdx.y * kRT, n0 = blockIdx.x * kRT;
+    const int kp = threadIdx.x & 63;   // pair of rows k0 + 2kp, k0 + 2kp + 1
+    const int c = threadIdx.x >> 6;    // columns n0 + 32c .. n0 + 32c + 31
+    uint4 x = make_uint4(0, 0, 0, 0), y = x;
+    const long col_byte = (n0 >> 1) + 16 * c;
+    if (col_byte < ((N + 1) >> 1)) {   // whole 16-byte pieces only: the launcher guarantees N % 32 == 0
+        if (k0 + 2 * kp < K) x = *reinterpret_cast<const uint4 *>(src + (k0 + 2L * kp) * ld_src + col_byte);
+        if (k0 + 2 * kp + 1 < K) y = *reinterpret_cast<const uint4 *>(src + (k0 + 2L * kp + 1) * ld_src + col_byte);
+    }
+    const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t even = (xs[d] & kLowNibbles) | ((ys[d] << 4) & 0xF0F0F0F0u);
+        const uint32_t odd = ((xs[d] >> 4) & kLowNibbles) | (ys[d] & 0xF0F0F0F0u);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            out[32 * c + 8 * d + 2 * j][kp] = static_cast<uint8_t>(even >> (8 * j));
+            out[32 * c + 8 * d + 2 * j + 1][kp] = static_cast<uint8_t>(odd >> (8 * j));
+        }
+    }
+    __syncthreads();
+    const int piece = threadIdx.x & 3;  // 16 bytes = 32 k values
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int n = (threadIdx.x >> 2) + 64 * pass;
+        const long kb = (k0 >> 1) + 16 * piece;
+        if (n0 + n < N && kb < ((K + 1) >> 1))  // K % 32 == 0: whole pieces
+            *reinterpret_cast<uint4 *>(dst + (n0 + static_cast<long>(n)) * ld_dst + kb) =
+                *reinterpret_cast<const uint4 *>(&out[n][16 * piece]);
+    }
+}
+
 // ---------------------------------------------------------------- depth sums
 // LANES lanes cooperate on one row; a wave holds 64 / LANES rows.
 template <int LANES>
@@ -328,6 +373,13 @@ hipError_t launch_pack(const uint8_t *src, int rows, int cols, int ld_src, int t
 hipError_t launch_repack_kn_to_nk(const uint8_t *B_kn, int K, int N, int ldb,
                                   uint8_t *B_nk, int ld_out, hipStream_t stream)
 {
+    const bool fast = (K % 32 == 0) && (N % 32 == 0) && (ldb % 16 == 0) && (ld_out % 16 == 0) &&
+                      (reinterpret_cast<uintptr_t>(B_kn) % 16 == 0) && (reinterpret_cast<uintptr_t>(B_nk) % 16 == 0);
+    if (fast) {
+        dim3 grid((N + kRT - 1) / kRT, (K + kRT - 1) / kRT);
+        repack_kn_to_nk_fast_kernel<<<grid, 256, 0, stream>>>(B_kn, K, N, ldb, B_nk, ld_out);
+        return hipGetLastError();
+    }
     dim3 grid((N + kT - 1) / kT, (K + kT - 1) / kT);
     repack_kn_to_nk_kernel<<<grid, 256, 0, stream>>>(B_kn, K, N, ldb, B_nk, ld_out);
     return hipGetLastError();
