@@ -229,6 +229,8 @@ int q4_conv2d_im2col(const q4_conv_desc *d, const uint8_t *x, int zx,
     p.g.OW = OW;
     p.g.zx = zx;
 
+    if (tile_override() < 0 && q4::conv_small_depth_applies(p.g, d->OC))
+        return rc_of(q4::launch_conv_small_depth(x, w, p.g, d->OC, zw, y, s));
     if (q4::launch_conv_rowsum(x, p.g, rowsum, s) != hipSuccess) return Q4_ERR_HIP;
     if (!w_colsum) {
         if (q4::launch_rowsum(w, d->OC, K, (K + 1) / 2, colsum, s) != hipSuccess) return Q4_ERR_HIP;

@@ -250,6 +250,64 @@ conv_rowsum_kernel(const uint8_t *__restrict__ x, ConvGeom g, long M, int32_t *_
     sums[m] = s;
 }
 
+
+// ---------------------------------------------------------------- small-depth convolution
+// For depths up to 32 codes (e.g. a 3x3 kernel on a single-channel image) the matrix cores have
+// nothing to chew on and the layer is bound by writing its int32 output.  One thread owns one
+// output pixel and walks its patch once per group of 16 output channels: each input code, offset
+// by the zero point (out-of-image taps are exactly 0), multiplies 16 offset weights read from LDS
+// with one 64-byte row -- the left-hand side of Eq. (2) of the paper evaluated directly, so no
+// depth sums are needed.
+constexpr int kSmallDepth = 32;
+constexpr int kOcGroup = 16;
+__global__ void __launch_bounds__(256)
+conv_small_depth_kernel(const uint8_t *__restrict__ x, const uint8_t *__restrict__ w, ConvGeom g, long M, int K,
+                        int OC, int oc_pad, int zw, int32_t *__restrict__ y)
+{
+    extern __shared__ __attribute__((aligned(16))) int wl[];  // K x oc_pad offset weights, depth-major
+    const int wrow = (K + 1) >> 1;
+    for (int i = threadIdx.x; i < K * oc_pad; i += 256) {
+        const int k = i / oc_pad, oc = i % oc_pad;
+        int v = 0;
+        if (oc < OC) v = static_cast<int>((w[static_cast<long>(oc) * wrow + (k >> 1)] >> (4 * (k & 1))) & 15) - zw;
+        wl[i] = v;
+    }
+    __syncthreads();
+    const long m = blockIdx.x * 256L + threadIdx.x;
+    if (m >= M) return;
+    const int ow = static_cast<int>(m % g.OW);
+    const long t = m / g.OW;
+    const int oh = static_cast<int>(t % g.OH);
+    const long pixel0 = (t / g.OH) * g.H * g.W;
+    int32_t *out = y + m * OC;
+    for (int oc0 = 0; oc0 < OC; oc0 += kOcGroup) {
+        int acc[kOcGroup];
+#pragma unroll
+        for (int j = 0; j < kOcGroup; ++j) acc[j] = 0;
+        int k = 0;
+        for (int kh = 0; kh < g.KH; ++kh)
+            for (int kw = 0; kw < g.KW; ++kw) {
+                const int ih = oh * g.sh + kh - g.ph, iw = ow * g.sw + kw - g.pw;
+                const bool inside = ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
+                const long e0 = (pixel0 + static_cast<long>(ih) * g.W + iw) * g.C;
+                for (int c = 0; c < g.C; ++c, ++k) {
+                    if (!inside) continue;
+                    const int v = static_cast<int>((x[(e0 + c) >> 1] >> (4 * ((e0 + c) & 1))) & 15) - g.zx;
+                    const vec4i *wr = reinterpret_cast<const vec4i *>(&wl[k * oc_pad + oc0]);
+#pragma unroll
+                    for (int q = 0; q < kOcGroup / 4; ++q) {
+                        const vec4i w4 = wr[q];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[4 * q + e] += v * w4[e];
+                    }
+                }
+            }
+#pragma unroll
+        for (int j = 0; j < kOcGroup; ++j)
+            if (oc0 + j < OC) out[oc0 + j] = acc[j];
+    }
+}
+
 // ---------------------------------------------------------------- re-quantization
 __device__ __forceinline__ uint32_t requant_one(int32_t acc, int32_t mult, int shift, int zo, int qmin, int qmax)
 {
@@ -402,6 +460,21 @@ hipError_t launch_conv_rowsum(const uint8_t *x, const ConvGeom &g, int32_t *sums
 {
     const long M = static_cast<long>(g.N) * g.OH * g.OW;
     conv_rowsum_kernel<<<grid_for(M), 256, 0, stream>>>(x, g, M, sums);
+    return hipGetLastError();
+}
+
+bool conv_small_depth_applies(const ConvGeom &g, int OC)
+{
+    return static_cast<long>(g.KH) * g.KW * g.C <= kSmallDepth && OC <= 256;  // 32 KB of LDS at most
+}
+
+hipError_t launch_conv_small_depth(const uint8_t *x, const uint8_t *w, const ConvGeom &g, int OC, int zw,
+                                   int32_t *y, hipStream_t stream)
+{
+    const long M = static_cast<long>(g.N) * g.OH * g.OW;
+    const int K = g.KH * g.KW * g.C;
+    const int oc_pad = (OC + kOcGroup - 1) / kOcGroup * kOcGroup;
+    conv_small_depth_kernel<<<grid_for(M), 256, static_cast<size_t>(K) * oc_pad * sizeof(int), stream>>>(x, w, g, M, K, OC, oc_pad, zw, y);
     return hipGetLastError();
 }
 

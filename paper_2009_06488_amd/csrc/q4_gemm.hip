@@ -33,7 +33,8 @@ enum LoadMode {
     kDenseAligned = 0,  // rows 16-byte aligned, ceil(K/2) a multiple of 16
     kDenseGeneric = 1,  // any alignment, any K
     kConvAligned = 2,   // C a multiple of 32: every 16-byte chunk lies inside one tap
-    kConvGeneric = 3    // any C: gathered code by code
+    kConvGeneric = 3,   // any C: gathered code by code
+    kConvHalf = 4       // C a multiple of 16: every 8-byte half chunk lies inside one tap; B by the general loader
 };
 
 struct KernelArgs {
@@ -135,6 +136,29 @@ __device__ __forceinline__ uint4 load_conv_chunk_aligned(const uint8_t *x, const
     return v;
 }
 
+// Eight bytes (16 channels of one tap) of the virtual im2col row when C % 16 == 0.
+__device__ __forceinline__ uint2 load_conv_half_chunk(const uint8_t *x, const ConvGeom &g,
+                                                      const PatchOrigin &o, int kb, int kbytes)
+{
+    uint2 v = make_uint2(0, 0);
+    if (kb < kbytes) {
+        const int kn = 2 * kb;
+        const int tap = kn / g.C;
+        const int c0 = kn - tap * g.C;
+        const int kh = tap / g.KW;
+        const int kw = tap - kh * g.KW;
+        const int ih = o.ih0 + kh, iw = o.iw0 + kw;
+        if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) {
+            const long e = ((o.pixel0 + static_cast<long>(ih) * g.W + iw) * g.C + c0) >> 1;
+            v = *reinterpret_cast<const uint2 *>(x + e);
+        } else {
+            const uint32_t f = static_cast<uint32_t>(g.zx) * 0x11111111u;
+            v = make_uint2(f, f);
+        }
+    }
+    return v;
+}
+
 // Same chunk for any channel count: eight codes per dword gathered one by one.
 __device__ __forceinline__ uint32_t load_conv_dword_generic(const uint8_t *x, const ConvGeom &g,
                                                             const PatchOrigin &o, int kn0, int K)
@@ -170,7 +194,7 @@ __device__ __forceinline__ uint32_t load_conv_dword_generic(const uint8_t *x, co
 // and then nothing hides the burst of C stores.  Holding back the second workgroup of each
 // compute unit once, at the start, breaks that symmetry: from then on one workgroup's stores
 // overlap the other's products.  The wait is bounded by the clock and by an iteration cap.
-__device__ __forceinline__ void stagger_start(const KernelArgs &p)
+[[maybe_unused]] __device__ __forceinline__ void stagger_start(const KernelArgs &p)
 {
     const int b = static_cast<int>(blockIdx.x) - p.stagger_first;
     if (p.stagger_ticks > 0 && b >= 0 && b < p.stagger_count) {
@@ -275,7 +299,7 @@ q4_gemm_kernel(const KernelArgs p)
     constexpr int NA = BM * kChunks / T, NB = BN * kChunks / T;
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 fragments");
     static_assert(BM * kChunks % T == 0 && BN * kChunks % T == 0, "tile rows must divide over the threads");
-    constexpr bool kConv = (MODE == kConvAligned || MODE == kConvGeneric);
+    constexpr bool kConv = (MODE == kConvAligned || MODE == kConvGeneric || MODE == kConvHalf);
     constexpr bool kAligned = (MODE == kDenseAligned || MODE == kConvAligned);
 
     __shared__ uint4 lds[kStages][(BM + BN) * kChunks];
@@ -335,6 +359,10 @@ q4_gemm_kernel(const KernelArgs p)
                 a_reg[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, present ? a_off[i] : kOutOfRange, k0, 0);
             } else if constexpr (MODE == kConvAligned) {
                 a_reg[i] = as_v4u(load_conv_chunk_aligned(p.A, p.g, a_org[i], kb, p.kbytes));
+            } else if constexpr (MODE == kConvHalf) {
+                const uint2 h0 = load_conv_half_chunk(p.A, p.g, a_org[i], kb, p.kbytes);
+                const uint2 h1 = load_conv_half_chunk(p.A, p.g, a_org[i], kb + 8, p.kbytes);
+                a_reg[i] = v4u{h0.x, h0.y, h1.x, h1.y};
             } else if constexpr (MODE == kConvGeneric) {
                 a_reg[i] = v4u{0, 0, 0, 0};
                 if (kb < p.kbytes) {
@@ -682,8 +710,11 @@ hipError_t launch_tile(const GemmProblem &q, hipStream_t stream)
             q4_gemm_kernel<BM, BN, WAVES_M, WAVES_N, kDenseGeneric><<<grid, block, 0, stream>>>(a);
     } else {
         const bool x_aligned = (reinterpret_cast<uintptr_t>(q.A) % 16 == 0) && (q.g.C % 32 == 0);
+        const bool x_half = (reinterpret_cast<uintptr_t>(q.A) % 8 == 0) && (q.g.C % 16 == 0);
         if (x_aligned && b_aligned)
             q4_gemm_kernel<BM, BN, WAVES_M, WAVES_N, kConvAligned><<<grid, block, 0, stream>>>(a);
+        else if (x_half)
+            q4_gemm_kernel<BM, BN, WAVES_M, WAVES_N, kConvHalf><<<grid, block, 0, stream>>>(a);
         else
             q4_gemm_kernel<BM, BN, WAVES_M, WAVES_N, kConvGeneric><<<grid, block, 0, stream>>>(a);
     }
@@ -696,11 +727,14 @@ hipError_t launch_gemm(const GemmProblem &p, int force_tile, hipStream_t stream)
 {
     int tile = force_tile;
     if (tile < 0) {
-        // Large tiles reuse operands best but need enough of them to fill 256 compute units.
-        const long t_large = ((p.M + 255L) / 256) * ((p.N + 255L) / 256);
-        const long t_medium = ((p.M + 127L) / 128) * ((p.N + 127L) / 128);
-        if (t_large >= 256) tile = 0;
-        else if (t_medium >= 128) tile = 1;
+        // The tile is as wide as the output needs (few output channels are the rule for
+        // convolutions) and as tall as still leaves enough tiles for 256 compute units.
+        auto tiles = [&](long bm, long bn) { return ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
+        if (p.N <= 32) tile = 7;
+        else if (p.N <= 64) tile = tiles(256, 64) >= 256 ? 6 : 2;
+        else if (p.N <= 128) tile = tiles(256, 128) >= 256 ? 3 : (tiles(128, 128) >= 128 ? 1 : 2);
+        else if (tiles(256, 256) >= 256) tile = 0;
+        else if (tiles(128, 128) >= 128) tile = 1;
         else tile = 2;
     }
     switch (tile) {
@@ -709,6 +743,8 @@ hipError_t launch_gemm(const GemmProblem &p, int force_tile, hipStream_t stream)
     case 3: return launch_tile<256, 128, 2, 2>(p, stream);
     case 4: return launch_tile<128, 256, 2, 2>(p, stream);
     case 5: return launch_tile<256, 256, 2, 2>(p, stream);
+    case 6: return launch_tile<256, 64, 4, 1>(p, stream);
+    case 7: return launch_tile<128, 32, 2, 1>(p, stream);
     default: return launch_tile<64, 64, 2, 2>(p, stream);
     }
 }

@@ -41,6 +41,10 @@ hipError_t launch_repack_kn_to_nk(const uint8_t *B_kn, int K, int N, int ldb,
                                   uint8_t *B_nk, int ld_out, hipStream_t stream);
 hipError_t launch_rowsum(const uint8_t *A, int rows, int k, long ld, int32_t *sums, hipStream_t stream);
 hipError_t launch_conv_rowsum(const uint8_t *x, const ConvGeom &g, int32_t *sums, hipStream_t stream);
+// Direct evaluation for depths KH*KW*C <= 32: no depth sums, no matrix cores.
+bool conv_small_depth_applies(const ConvGeom &g, int OC);
+hipError_t launch_conv_small_depth(const uint8_t *x, const uint8_t *w, const ConvGeom &g, int OC, int zw,
+                                   int32_t *y, hipStream_t stream);
 hipError_t launch_requant(const int32_t *acc, long rows, int cols, long ld_acc,
                           int32_t mult, int shift, int zo, int qmin, int qmax,
                           uint8_t *out, long ld_out, hipStream_t stream);
