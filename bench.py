@@ -211,6 +211,8 @@ def _extras(q4, wl, torch, np, dev):
 
     ms = _time_ms(conv_step, torch)
     ex["cfg3_conv_requant_us"] = round(ms * 1e3, 2)
+    ms_f = _time_ms(lambda: q4.q4_conv2d_requant(d, x, c.zx, w, c.zw, c.mult, c.shift, c.zo, out=qo, workspace=wsc), torch)
+    ex["cfg3_conv_requant_fused_us"] = round(ms_f * 1e3, 2)
     ex["cfg3_tops"] = round(2.0 * y.shape[0] * c.OC * c.depth / (ms * 1e-3) / 1e12, 3)
 
     # config 4: OCR-style CNN, batch 64
@@ -218,13 +220,16 @@ def _extras(q4, wl, torch, np, dev):
     act0 = flat_pack(case.x_codes)
     weights = [q4.q4_pack(torch.from_numpy(L.w_codes.reshape(L.cout, -1)).to(dev)) for L in case.layers]
 
-    def cnn_step():
+    def cnn_step(fused=False):
         act, zx, cin, H, W = act0, case.zx, 1, case.H, case.W
         for L, wt in zip(case.layers, weights):
             dd = q4.conv_desc(case.batch, H, W, cin, 3, 3, (1, 1), (case.pad, case.pad), L.cout)
-            yy = q4.q4_conv2d_im2col(dd, act, zx, wt, L.zw)
             H, W = q4.conv_out_hw(dd)
-            act = q4.q4_requant(yy, L.mult, L.shift, L.zo).reshape(-1)
+            if fused:
+                act = q4.q4_conv2d_requant(dd, act, zx, wt, L.zw, L.mult, L.shift, L.zo).reshape(-1)
+            else:
+                yy = q4.q4_conv2d_im2col(dd, act, zx, wt, L.zw)
+                act = q4.q4_requant(yy, L.mult, L.shift, L.zo).reshape(-1)
             zx, cin = L.zo, L.cout
             if L.pool_after:
                 act = q4.q4_maxpool2x2(act, case.batch, H, W, cin)
@@ -234,6 +239,9 @@ def _extras(q4, wl, torch, np, dev):
     ms = _time_ms(cnn_step, torch, reps=10)
     ex["cfg4_cnn_forward_ms"] = round(ms, 4)
     ex["cfg4_images_per_s"] = round(case.batch / (ms * 1e-3), 1)
+    ms = _time_ms(lambda: cnn_step(fused=True), torch, reps=10)
+    ex["cfg4_cnn_forward_fused_requant_ms"] = round(ms, 4)
+    ex["cfg4_images_per_s_fused_requant"] = round(case.batch / (ms * 1e-3), 1)
     return ex
 
 

@@ -164,6 +164,20 @@ int q4_conv2d_im2col(const q4_conv_desc *desc, const uint8_t *x, int zx,
                      int32_t *y, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * q4_conv2d_requant -- q4_conv2d_im2col followed by q4_requant in one pass: the
+ * int32 layer output never goes to memory (the per-layer re-quantization is what
+ * the paper names as the cost that remains beside the multiplication, Sec. 4.2).
+ * Result identical to calling the two in sequence.
+ *   out : (N*OH*OW) rows of ceil(OC/2) bytes (tightly packed rows): NHWC packed
+ *         codes, the input format of the next layer.
+ * Other arguments as in q4_conv2d_im2col and q4_requant.
+ */
+int q4_conv2d_requant(const q4_conv_desc *desc, const uint8_t *x, int zx,
+                      const uint8_t *w, int zw, const int32_t *w_colsum,
+                      int32_t mult, int shift, int zo, int qmin, int qmax,
+                      uint8_t *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * q4_requant -- bring an int32 layer output back to 4-bit codes for the next
  * quantized layer (the Q -> Q transition of Sec. 3.2), in integer form:
  *   out(r, c) = min(max(floor(acc[r*ld_acc + c] * mult / 2^shift) + zo, qmin), qmax)

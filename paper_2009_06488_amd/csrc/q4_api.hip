@@ -191,14 +191,14 @@ size_t q4_conv2d_workspace_bytes(const q4_conv_desc *d)
 {
     int OH, OW;
     if (!d || !conv_out_dims(d, &OH, &OW)) return 0;
-    return align_up(4 * (static_cast<size_t>(d->N) * OH * OW + static_cast<size_t>(d->OC)), 16);
+    return align_up(4 * static_cast<size_t>(d->OC), 16);  // the weight sums; input row sums are formed in the kernel
 }
 
-int q4_conv2d_im2col(const q4_conv_desc *d, const uint8_t *x, int zx,
-                     const uint8_t *w, int zw, const int32_t *w_colsum,
-                     int32_t *y, void *workspace, size_t workspace_bytes, void *stream)
+// Shared body of q4_conv2d_im2col (rq.out == NULL, int32 result to y) and q4_conv2d_requant.
+static int conv_forward(const q4_conv_desc *d, const uint8_t *x, int zx, const uint8_t *w, int zw,
+                        const int32_t *w_colsum, int32_t *y, const q4::Requant &rq,
+                        void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!d || !x || !w || !y) return Q4_ERR_NULL;
     int OH, OW;
     if (!conv_out_dims(d, &OH, &OW)) return Q4_ERR_SHAPE;
     if (!code_ok(zx) || !code_ok(zw)) return Q4_ERR_RANGE;
@@ -211,8 +211,7 @@ int q4_conv2d_im2col(const q4_conv_desc *d, const uint8_t *x, int zx,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int M = d->N * OH * OW;
     const int K = static_cast<int>(depth);
-    int32_t *rowsum = static_cast<int32_t *>(workspace);
-    int32_t *colsum = rowsum + M;
+    int32_t *colsum = static_cast<int32_t *>(workspace);
 
     q4::GemmProblem p{};
     p.g.N = d->N;
@@ -228,10 +227,10 @@ int q4_conv2d_im2col(const q4_conv_desc *d, const uint8_t *x, int zx,
     p.g.OH = OH;
     p.g.OW = OW;
     p.g.zx = zx;
+    p.rq = rq;
 
     if (tile_override() < 0 && q4::conv_small_depth_applies(p.g, d->OC))
-        return rc_of(q4::launch_conv_small_depth(x, w, p.g, d->OC, zw, y, s));
-    if (q4::launch_conv_rowsum(x, p.g, rowsum, s) != hipSuccess) return Q4_ERR_HIP;
+        return rc_of(q4::launch_conv_small_depth(x, w, p.g, d->OC, zw, y, rq, s));
     if (!w_colsum) {
         if (q4::launch_rowsum(w, d->OC, K, (K + 1) / 2, colsum, s) != hipSuccess) return Q4_ERR_HIP;
         w_colsum = colsum;
@@ -245,12 +244,41 @@ int q4_conv2d_im2col(const q4_conv_desc *d, const uint8_t *x, int zx,
     p.ldb = (K + 1) / 2;
     p.C = y;
     p.ldc = d->OC;
-    p.rowsumA = rowsum;
+    p.rowsumA = nullptr;  // formed inside the kernel while the patches are gathered
     p.colsumB = w_colsum;
     p.za = zx;
     p.zb = zw;
     p.is_conv = true;
     return rc_of(q4::launch_gemm(p, tile_override(), s));
+}
+
+int q4_conv2d_im2col(const q4_conv_desc *d, const uint8_t *x, int zx,
+                     const uint8_t *w, int zw, const int32_t *w_colsum,
+                     int32_t *y, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!d || !x || !w || !y) return Q4_ERR_NULL;
+    const q4::Requant none{};
+    return conv_forward(d, x, zx, w, zw, w_colsum, y, none, workspace, workspace_bytes, stream);
+}
+
+int q4_conv2d_requant(const q4_conv_desc *d, const uint8_t *x, int zx,
+                      const uint8_t *w, int zw, const int32_t *w_colsum,
+                      int32_t mult, int shift, int zo, int qmin, int qmax,
+                      uint8_t *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!d || !x || !w || !out) return Q4_ERR_NULL;
+    if (mult < 0 || shift < 0 || shift > 62) return Q4_ERR_RANGE;
+    if (!code_ok(zo) || !code_ok(qmin) || !code_ok(qmax) || qmin > qmax) return Q4_ERR_RANGE;
+    if (d->OC <= 0) return Q4_ERR_SHAPE;
+    q4::Requant rq{};
+    rq.out = out;
+    rq.ld_out = (d->OC + 1) / 2;
+    rq.mult = mult;
+    rq.shift = shift;
+    rq.zo = zo;
+    rq.qmin = qmin;
+    rq.qmax = qmax;
+    return conv_forward(d, x, zx, w, zw, w_colsum, nullptr, rq, workspace, workspace_bytes, stream);
 }
 
 int q4_requant(const int32_t *acc, long rows, int cols, long ld_acc,

@@ -215,41 +215,16 @@ rowsum_kernel(const uint8_t *__restrict__ A, int rows, int k, long ld, int32_t *
     if (r < rows && sub == 0) sums[r] = s;
 }
 
-// Row sums of the virtual im2col matrix: one thread per output pixel, taps outside
-// the image count C * zx (they read as the zero-point code).
-__global__ void __launch_bounds__(256)
-conv_rowsum_kernel(const uint8_t *__restrict__ x, ConvGeom g, long M, int32_t *__restrict__ sums)
+// Integer re-quantization of one accumulator (see q4_requant): the 64-bit product is exact and >>
+// on a signed 64-bit value is an arithmetic shift, i.e. the floor.
+__device__ __forceinline__ uint32_t requant_one(int32_t acc, int32_t mult, int shift, int zo, int qmin, int qmax)
 {
-    const long m = blockIdx.x * 256L + threadIdx.x;
-    if (m >= M) return;
-    const int ow = static_cast<int>(m % g.OW);
-    const long t = m / g.OW;
-    const int oh = static_cast<int>(t % g.OH);
-    const long n = t / g.OH;
-    int s = 0;
-    for (int kh = 0; kh < g.KH; ++kh) {
-        const int ih = oh * g.sh + kh - g.ph;
-        for (int kw = 0; kw < g.KW; ++kw) {
-            const int iw = ow * g.sw + kw - g.pw;
-            if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) {
-                s += g.C * g.zx;
-                continue;
-            }
-            const long e0 = ((n * g.H + ih) * g.W + iw) * g.C;  // first code of the pixel
-            if ((g.C & 7) == 0 && (reinterpret_cast<uintptr_t>(x) & 3u) == 0) {
-                const uint32_t *p = reinterpret_cast<const uint32_t *>(x + (e0 >> 1));
-                for (int c = 0; c < g.C / 8; ++c) s += nibble_sum8(p[c]);
-            } else {
-                for (int c = 0; c < g.C; ++c) {
-                    const long e = e0 + c;
-                    s += (x[e >> 1] >> (4 * (e & 1))) & 15;
-                }
-            }
-        }
-    }
-    sums[m] = s;
+    long long q = (static_cast<long long>(acc) * static_cast<long long>(mult)) >> shift;
+    q += zo;
+    q = q < qmin ? qmin : q;
+    q = q > qmax ? qmax : q;
+    return static_cast<uint32_t>(q);
 }
-
 
 // ---------------------------------------------------------------- small-depth convolution
 // For depths up to 32 codes (e.g. a 3x3 kernel on a single-channel image) the matrix cores have
@@ -262,9 +237,11 @@ constexpr int kSmallDepth = 32;
 constexpr int kOcGroup = 16;
 __global__ void __launch_bounds__(256)
 conv_small_depth_kernel(const uint8_t *__restrict__ x, const uint8_t *__restrict__ w, ConvGeom g, long M, int K,
-                        int OC, int oc_pad, int zw, int32_t *__restrict__ y)
+                        int OC, int oc_pad, int zw, int32_t *__restrict__ y, Requant rq)
 {
-    extern __shared__ __attribute__((aligned(16))) int wl[];  // K x oc_pad offset weights, depth-major
+    extern __shared__ __attribute__((aligned(16))) int smem[];
+    int *wl = smem;                       // K x oc_pad offset weights, depth-major
+    int *stage = smem + K * oc_pad;       // 256 x kOcGroup results of the block, for coalesced stores
     const int wrow = (K + 1) >> 1;
     for (int i = threadIdx.x; i < K * oc_pad; i += 256) {
         const int k = i / oc_pad, oc = i % oc_pad;
@@ -273,13 +250,15 @@ conv_small_depth_kernel(const uint8_t *__restrict__ x, const uint8_t *__restrict
         wl[i] = v;
     }
     __syncthreads();
-    const long m = blockIdx.x * 256L + threadIdx.x;
-    if (m >= M) return;
-    const int ow = static_cast<int>(m % g.OW);
-    const long t = m / g.OW;
+    const long m_block = blockIdx.x * 256L;
+    const long m = m_block + threadIdx.x;
+    const bool active = m < M;
+    const long mm = active ? m : M - 1;
+    const int ow = static_cast<int>(mm % g.OW);
+    const long t = mm / g.OW;
     const int oh = static_cast<int>(t % g.OH);
     const long pixel0 = (t / g.OH) * g.H * g.W;
-    int32_t *out = y + m * OC;
+    const bool vec_store = (OC % 4 == 0) && (reinterpret_cast<uintptr_t>(y) % 16 == 0);
     for (int oc0 = 0; oc0 < OC; oc0 += kOcGroup) {
         int acc[kOcGroup];
 #pragma unroll
@@ -302,22 +281,48 @@ conv_small_depth_kernel(const uint8_t *__restrict__ x, const uint8_t *__restrict
                     }
                 }
             }
+        if (rq.out != nullptr) {
+            // fused re-quantization: this thread's 16 codes are 8 consecutive output bytes
+            if (active) {
+                uint8_t *dst = rq.out + m * rq.ld_out + (oc0 >> 1);
 #pragma unroll
-        for (int j = 0; j < kOcGroup; ++j)
-            if (oc0 + j < OC) out[oc0 + j] = acc[j];
+                for (int j = 0; j < kOcGroup; j += 2) {
+                    if (oc0 + j >= OC) break;
+                    uint32_t v = requant_one(acc[j], rq.mult, rq.shift, rq.zo, rq.qmin, rq.qmax);
+                    if (oc0 + j + 1 < OC) v |= requant_one(acc[j + 1], rq.mult, rq.shift, rq.zo, rq.qmin, rq.qmax) << 4;
+                    dst[j >> 1] = static_cast<uint8_t>(v);
+                }
+            }
+            continue;
+        }
+        // int32 output: through LDS so that a wave writes whole 64-byte pieces of consecutive rows
+#pragma unroll
+        for (int q = 0; q < kOcGroup / 4; ++q)
+            *reinterpret_cast<vec4i *>(&stage[threadIdx.x * kOcGroup + 4 * q]) =
+                vec4i{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kOcGroup / 4; ++i) {
+            const int idx = threadIdx.x + 256 * i;
+            const int px = idx / (kOcGroup / 4), piece = idx % (kOcGroup / 4);
+            const long row = m_block + px;
+            const int oc = oc0 + 4 * piece;
+            if (row < M && oc < OC) {
+                const vec4i v = *reinterpret_cast<const vec4i *>(&stage[px * kOcGroup + 4 * piece]);
+                int32_t *dst = y + row * OC + oc;
+                if (vec_store) {
+                    *reinterpret_cast<vec4i *>(dst) = v;
+                } else {
+                    for (int e = 0; e < 4; ++e)
+                        if (oc + e < OC) dst[e] = v[e];
+                }
+            }
+        }
+        __syncthreads();
     }
 }
 
 // ---------------------------------------------------------------- re-quantization
-__device__ __forceinline__ uint32_t requant_one(int32_t acc, int32_t mult, int shift, int zo, int qmin, int qmax)
-{
-    // exact 64-bit product; >> on a signed 64-bit value is an arithmetic shift, i.e. floor
-    long long q = (static_cast<long long>(acc) * static_cast<long long>(mult)) >> shift;
-    q += zo;
-    q = q < qmin ? qmin : q;
-    q = q > qmax ? qmax : q;
-    return static_cast<uint32_t>(q);
-}
 
 // Fast path: one thread turns 8 accumulators (two 16-byte loads) into one packed dword.
 __global__ void __launch_bounds__(256)
@@ -456,25 +461,19 @@ hipError_t launch_rowsum(const uint8_t *A, int rows, int k, long ld, int32_t *su
     return hipGetLastError();
 }
 
-hipError_t launch_conv_rowsum(const uint8_t *x, const ConvGeom &g, int32_t *sums, hipStream_t stream)
-{
-    const long M = static_cast<long>(g.N) * g.OH * g.OW;
-    conv_rowsum_kernel<<<grid_for(M), 256, 0, stream>>>(x, g, M, sums);
-    return hipGetLastError();
-}
-
 bool conv_small_depth_applies(const ConvGeom &g, int OC)
 {
     return static_cast<long>(g.KH) * g.KW * g.C <= kSmallDepth && OC <= 256;  // 32 KB of LDS at most
 }
 
 hipError_t launch_conv_small_depth(const uint8_t *x, const uint8_t *w, const ConvGeom &g, int OC, int zw,
-                                   int32_t *y, hipStream_t stream)
+                                   int32_t *y, const Requant &rq, hipStream_t stream)
 {
     const long M = static_cast<long>(g.N) * g.OH * g.OW;
     const int K = g.KH * g.KW * g.C;
     const int oc_pad = (OC + kOcGroup - 1) / kOcGroup * kOcGroup;
-    conv_small_depth_kernel<<<grid_for(M), 256, static_cast<size_t>(K) * oc_pad * sizeof(int), stream>>>(x, w, g, M, K, OC, oc_pad, zw, y);
+    const size_t lds_bytes = (static_cast<size_t>(K) * oc_pad + 256 * kOcGroup) * sizeof(int);
+    conv_small_depth_kernel<<<grid_for(M), 256, lds_bytes, stream>>>(x, w, g, M, K, OC, oc_pad, zw, y, rq);
     return hipGetLastError();
 }
 

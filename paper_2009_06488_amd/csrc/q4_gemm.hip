@@ -51,6 +51,7 @@ struct KernelArgs {
     int tiles_m, tiles_n;
     int stagger_first, stagger_count;  // workgroups [first, first + count) start late by stagger_ticks
     int stagger_ticks;                 // in ticks of the 100 MHz wall clock
+    Requant rq;  // when rq.out is set the epilogue re-quantizes and writes packed codes instead of C
     ConvGeom g;
 };
 
@@ -238,10 +239,11 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
 // ---- epilogue shared by both kernels.  The zero-point terms of Eq. (2) are staged in LDS
 // once per tile, before the main loop: row_term[r] = -zb * rowsumA[m0 + r] and
 // col_term[c] = K * za * zb - za * colsumB[n0 + c], so that C = raw + row_term + col_term.
-template <int BM, int BN, int T>
+template <int BM, int BN, int T, bool ROWS = true>
 __device__ __forceinline__ void stage_terms(int *terms, const KernelArgs &p, int m0, int n0, int tid)
 {
-    for (int r = tid; r < BM; r += T) terms[r] = (m0 + r < p.M) ? -p.zb * p.rowsumA[m0 + r] : 0;
+    if constexpr (ROWS)
+        for (int r = tid; r < BM; r += T) terms[r] = (m0 + r < p.M) ? -p.zb * p.rowsumA[m0 + r] : 0;
     const int kzz = p.K * p.za * p.zb;
     for (int c = tid; c < BN; c += T) terms[BM + c] = (n0 + c < p.N) ? kzz - p.za * p.colsumB[n0 + c] : 0;
 }
@@ -271,6 +273,58 @@ __device__ __forceinline__ void store_tile(const v16i (&acc)[FM][FN], const int 
                     if (interior || (m_wave + r + e < p.M && n < p.N)) dst[e * p.ldc] = value;
                 }
             }
+        }
+    }
+}
+
+
+// Integer re-quantization of one value: floor(acc * mult / 2^shift) + zo, clamped.  The 64-bit
+// product is exact and >> on a signed 64-bit value is an arithmetic shift, i.e. the floor.
+__device__ __forceinline__ uint32_t requant_code(int acc, const Requant &rq)
+{
+    long long q = (static_cast<long long>(acc) * static_cast<long long>(rq.mult)) >> rq.shift;
+    q += rq.zo;
+    q = q < rq.qmin ? rq.qmin : q;
+    q = q > rq.qmax ? rq.qmax : q;
+    return static_cast<uint32_t>(q);
+}
+
+// Fused epilogue: corrected accumulators -> codes, one per byte, into an LDS tile laid out as the
+// output (BM rows of BN codes); after a barrier the workgroup packs them two per byte and
+// stores whole rows of the tile.  `stage` may alias the operand ring (all reads of it are done).
+template <int BM, int BN, int FM, int FN, int T>
+__device__ __forceinline__ void store_tile_requant(const v16i (&acc)[FM][FN], const int *terms, uint8_t *stage,
+                                                   const KernelArgs &p, int m0, int n0, int row_wave, int col_wave,
+                                                   int lane, int tid)
+{
+    constexpr int kPitch = BN + 4;  // bytes per staged row
+    const int frow = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        const int c = col_wave + j * 32 + frow;
+        const int col_term = terms[BM + c];
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int r = row_wave + i * 32 + 8 * q + 4 * half;
+                const v4i row_term = *reinterpret_cast<const v4i *>(&terms[r]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    stage[(r + e) * kPitch + c] = static_cast<uint8_t>(requant_code(acc[i][j][4 * q + e] + col_term + row_term[e], p.rq));
+            }
+        }
+    }
+    __syncthreads();
+    // one thread per output byte (two codes); consecutive threads write consecutive bytes of a row
+    constexpr int kRowBytes = BN / 2;
+    for (int idx = tid; idx < BM * kRowBytes; idx += T) {
+        const int r = idx / kRowBytes, b = idx % kRowBytes;
+        const int m = m0 + r, n = n0 + 2 * b;
+        if (m < p.M && n < p.N) {
+            uint32_t v = stage[r * kPitch + 2 * b];
+            if (n + 1 < p.N) v |= static_cast<uint32_t>(stage[r * kPitch + 2 * b + 1]) << 4;
+            p.rq.out[static_cast<long>(m) * p.rq.ld_out + (n >> 1)] = static_cast<uint8_t>(v);
         }
     }
 }
@@ -314,7 +368,8 @@ q4_gemm_kernel(const KernelArgs p)
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const bool odd_k = (p.K & 1) != 0;
-    stage_terms<BM, BN, T>(terms, p, m0, n0, tid);  // published by the barriers of the main loop
+    // published by the barriers of the main loop; convolutions sum their gathered rows themselves
+    stage_terms<BM, BN, T, !kConv>(terms, p, m0, n0, tid);
 
     // ---- what this thread copies from HBM to LDS at every step: NA chunks of A, NB of B.
     // Rows past M (or N) repeat the last valid row; their products are never stored.
@@ -349,6 +404,9 @@ q4_gemm_kernel(const KernelArgs p)
     if constexpr (kAligned) b_rsrc = make_rsrc(p.B, p.b_bytes);
 
     v4u a_reg[NA], b_reg[NB];
+    int a_sum[NA];  // convolution: running sum of the codes this thread has gathered for each of its rows
+#pragma unroll
+    for (int i = 0; i < NA; ++i) a_sum[i] = 0;
     auto fetch = [&](int kt) {
         const int k0 = kt * kStepBytes;
         const int kb = k0 + chunk * 16;
@@ -374,6 +432,18 @@ q4_gemm_kernel(const KernelArgs p)
             } else {
                 a_reg[i] = as_v4u(load_dense_chunk_generic(a_row[i], kb, p.kbytes, odd_k));
             }
+        }
+        if constexpr (kConv) {
+#pragma unroll
+            for (int i = 0; i < NA; ++i)
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const uint32_t w = a_reg[i][d];
+                    uint32_t t = (w & kLowNibbles) + ((w >> 4) & kLowNibbles);  // four byte sums, each <= 30
+                    t += t >> 16;
+                    t += t >> 8;
+                    a_sum[i] += static_cast<int>(t & 0xFFu);
+                }
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
@@ -473,7 +543,24 @@ q4_gemm_kernel(const KernelArgs p)
     }
 
     // ---- epilogue: add the zero-point terms of Eq. (2) and store
-    store_tile<BM, FM, FN>(acc, terms, p, m0 + wm * WM, n0 + wn * WN, wm * WM, wn * WN, lane);
+    if constexpr (kConv) {
+        // Row sums of the virtual im2col matrix (Sec. 2.2 of the paper: computed while unrolling):
+        // the four threads that gathered the four chunks of a row are neighbours in the wave.
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            int sum = a_sum[i];
+            sum += __shfl_xor(sum, 1, 64);
+            sum += __shfl_xor(sum, 2, 64);
+            const int row = (tid + i * T) / kChunks;
+            if (chunk == 0) terms[row] = (m0 + row < p.M) ? -p.zb * sum : 0;
+        }
+        __syncthreads();
+    }
+    if (p.rq.out != nullptr)
+        store_tile_requant<BM, BN, FM, FN, T>(acc, terms, reinterpret_cast<uint8_t *>(&lds[0][0]), p, m0, n0,
+                                              wm * WM, wn * WN, lane, tid);
+    else
+        store_tile<BM, FM, FN>(acc, terms, p, m0 + wm * WM, n0 + wn * WN, wm * WM, wn * WN, lane);
 
 }
 
@@ -677,6 +764,7 @@ hipError_t launch_tile(const GemmProblem &q, hipStream_t stream)
     a.tiles_m = (q.M + BM - 1) / BM;
     a.tiles_n = (q.N + BN - 1) / BN;
     a.g = q.g;
+    a.rq = q.rq;
     // Stagger only when two workgroups share a compute unit and there are several rounds of tiles.
     constexpr int kComputeUnits = 256;
     constexpr bool kTwoPerCu = min_waves_per_simd(BM / WAVES_M, BN / WAVES_N) == 2 && WAVES_M * WAVES_N == 4;

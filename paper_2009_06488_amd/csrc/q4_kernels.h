@@ -16,6 +16,14 @@ struct ConvGeom {
     int zx;  // code read for taps outside the image
 };
 
+// Optional fused re-quantization of the result (see q4_requant): when `out` is set the epilogue
+// writes packed codes there instead of int32 values to C.
+struct Requant {
+    uint8_t *out;   // M rows of ceil(N/2) bytes, or nullptr
+    long ld_out;    // bytes between rows
+    int mult, shift, zo, qmin, qmax;
+};
+
 struct GemmProblem {
     int M, N, K;
     const uint8_t *A;   // dense: M rows of ceil(K/2) bytes; conv: flat packed NHWC input
@@ -29,6 +37,7 @@ struct GemmProblem {
     int za, zb;
     bool is_conv;
     ConvGeom g;         // used when is_conv
+    Requant rq;         // convolution only
 };
 
 // Main product + zero-point epilogue: C = raw - za*colsumB[n] - zb*rowsumA[m] + K*za*zb.
@@ -40,11 +49,10 @@ hipError_t launch_pack(const uint8_t *src, int rows, int cols, int ld_src, int t
 hipError_t launch_repack_kn_to_nk(const uint8_t *B_kn, int K, int N, int ldb,
                                   uint8_t *B_nk, int ld_out, hipStream_t stream);
 hipError_t launch_rowsum(const uint8_t *A, int rows, int k, long ld, int32_t *sums, hipStream_t stream);
-hipError_t launch_conv_rowsum(const uint8_t *x, const ConvGeom &g, int32_t *sums, hipStream_t stream);
 // Direct evaluation for depths KH*KW*C <= 32: no depth sums, no matrix cores.
 bool conv_small_depth_applies(const ConvGeom &g, int OC);
 hipError_t launch_conv_small_depth(const uint8_t *x, const uint8_t *w, const ConvGeom &g, int OC, int zw,
-                                   int32_t *y, hipStream_t stream);
+                                   int32_t *y, const Requant &rq, hipStream_t stream);
 hipError_t launch_requant(const int32_t *acc, long rows, int cols, long ld_acc,
                           int32_t mult, int shift, int zo, int qmin, int qmax,
                           uint8_t *out, long ld_out, hipStream_t stream);

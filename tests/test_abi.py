@@ -43,7 +43,7 @@ def test_workspace_queries():
     assert q4.gemm_workspace_bytes(0, 32, 72, q4.B_NK) == 0
     assert q4.gemm_workspace_bytes(1, 1, 1, 5) == 0
     d = q4.conv_desc(1, 64, 64, 32, 3, 3, (1, 1), (1, 1), 64)
-    assert q4.conv2d_workspace_bytes(d) == 4 * (4096 + 64)
+    assert q4.conv2d_workspace_bytes(d) == 4 * 64
     assert q4.conv2d_workspace_bytes(q4.conv_desc(1, 2, 2, 1, 3, 3, (1, 1), (0, 0), 1)) == 0   # kernel larger than image
 
 
@@ -94,6 +94,8 @@ def test_other_argument_errors():
     ref = ctypes.byref(d)
     assert L.q4_conv2d_im2col(None, FAKE, 0, FAKE, 0, None, FAKE, FAKE, 1 << 20, None) == q4.ERR_NULL
     assert L.q4_conv2d_im2col(ref, FAKE, 16, FAKE, 0, None, FAKE, FAKE, 1 << 20, None) == q4.ERR_RANGE
-    assert L.q4_conv2d_im2col(ref, FAKE, 0, FAKE, 0, None, FAKE, FAKE, 16, None) == q4.ERR_WORKSPACE
+    assert L.q4_conv2d_im2col(ref, FAKE, 0, FAKE, 0, None, FAKE, FAKE, 8, None) == q4.ERR_WORKSPACE
+    assert L.q4_conv2d_requant(ref, FAKE, 0, FAKE, 0, None, 1, 63, 8, 0, 15, FAKE, FAKE, 1 << 20, None) == q4.ERR_RANGE
+    assert L.q4_conv2d_requant(ref, FAKE, 0, FAKE, 0, None, 1, 20, 8, 0, 15, None, FAKE, 1 << 20, None) == q4.ERR_NULL
     bad = q4.conv_desc(1, 8, 8, 4, 3, 3, (0, 1), (1, 1), 4)
     assert L.q4_conv2d_im2col(ctypes.byref(bad), FAKE, 0, FAKE, 0, None, FAKE, FAKE, 1 << 20, None) == q4.ERR_SHAPE

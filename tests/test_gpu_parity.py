@@ -214,6 +214,16 @@ def run_conv_case(c, tiles=(-1,)):
     # precomputed weight sums give the same result
     cs = q4.q4_rowsum(dw, c.depth)
     assert np.array_equal(host(q4.q4_conv2d_im2col(d, dx, c.zx, dw, c.zw, w_colsum=cs)), want)
+    # fused convolution + re-quantization == the two oracle steps in sequence (also with a ReLU clamp)
+    for qmin in (0, c.zo):
+        wantq = o.requant(want, c.mult, c.shift, c.zo, qmin, 15)
+        for tile in tiles:
+            q4.debug_force_tile(tile)
+            try:
+                gotq = host(q4.q4_conv2d_requant(d, dx, c.zx, dw, c.zw, c.mult, c.shift, c.zo, qmin, 15))
+            finally:
+                q4.debug_force_tile(-1)
+            assert np.array_equal(gotq, wantq), (c.name, tile, qmin)
     return want
 
 
@@ -326,15 +336,18 @@ def cnn_forward_oracle(case, x_codes):
     return act, (N, H, W, cin)
 
 
-def cnn_forward_gpu(case, x_codes):
+def cnn_forward_gpu(case, x_codes, fused=False):
     N, H, W = x_codes.shape[0], case.H, case.W
     act, zx, cin = dev(flat_pack(x_codes)), case.zx, 1
     for L in case.layers:
         w = dev(o.pack(L.w_codes.reshape(L.cout, -1)))
         d = q4.conv_desc(N, H, W, cin, 3, 3, (1, 1), (case.pad, case.pad), L.cout)
-        y = q4.q4_conv2d_im2col(d, act, zx, w, L.zw)
         H, W = q4.conv_out_hw(d)
-        act = q4.q4_requant(y, L.mult, L.shift, L.zo).reshape(-1)
+        if fused:
+            act = q4.q4_conv2d_requant(d, act, zx, w, L.zw, L.mult, L.shift, L.zo).reshape(-1)
+        else:
+            y = q4.q4_conv2d_im2col(d, act, zx, w, L.zw)
+            act = q4.q4_requant(y, L.mult, L.shift, L.zo).reshape(-1)
         zx, cin = L.zo, L.cout
         if L.pool_after:
             act = q4.q4_maxpool2x2(act, N, H, W, cin)
@@ -350,6 +363,8 @@ def test_cnn_config4_small_batch(pad):
     got, shape_g = cnn_forward_gpu(case, case.x_codes)
     assert shape_w == shape_g == ((2, 8, 32, 128) if pad == 1 else (2, 1, 25, 128))
     assert np.array_equal(got, want)
+    got_fused, _ = cnn_forward_gpu(case, case.x_codes, fused=True)
+    assert np.array_equal(got_fused, want)
     hist = np.bincount(o.unpack(want, want.size * 2), minlength=16)
     assert hist[1:15].sum() > 0.3 * want.size * 2       # the last layer is not saturated
 
@@ -359,6 +374,8 @@ def test_cnn_config4_full_batch_sampled_images():
     case = wl.config4(batch=64)
     say(case.name, "full batch, sampled images")
     got, (N, H, W, C) = cnn_forward_gpu(case, case.x_codes)
+    got_fused, _ = cnn_forward_gpu(case, case.x_codes, fused=True)
+    assert np.array_equal(got, got_fused)
     per = H * W * C // 2
     for img in (0, 31, 63):
         want, _ = cnn_forward_oracle(case, case.x_codes[img:img + 1])
