@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--size", type=int, default=8192, help="M = N = K (default: the benchmark's 8192)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a 256 MiB fill and a 256 MiB read-modify-write (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -66,6 +68,12 @@ def main():
     Bkn = torch.from_numpy(c.b_packed_kn).to(dev)
     C = torch.empty((M, N), dtype=torch.int32, device=dev)
     ws = torch.empty(q4.gemm_workspace_bytes(M, N, K, q4.B_KN), dtype=torch.uint8, device=dev)
+
+    if args.copy_probe:
+        probe = torch.ones(64 * 1024 * 1024, dtype=torch.int32, device=dev)   # fill: writes 256 MiB
+        probe.add_(1)                                                           # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del probe
 
     def step():
         q4.q4_gemm(A, c.za, Bkn, c.zb, M, N, K, q4.B_KN, out=C, workspace=ws)
