@@ -215,7 +215,28 @@ __device__ __forceinline__ void block_barrier()
 // The widening step: even depth positions (low nibbles) and odd ones (high nibbles) of
 // four packed dwords, each as sixteen int8 lanes for the matrix cores.
 __device__ __forceinline__ v4i low_codes(const v4u &p) { return (v4i)(p & kLowNibbles); }
-__device__ __forceinline__ v4i high_codes(const v4u &p) { return (v4i)((p >> 4) & kLowNibbles); }
+// The shift runs on 64-bit register pairs (v_lshrrev_b64 issues at the 32-bit rate, so one
+// instruction serves two dwords): the nibble that crosses from the upper dword into bits 31:28
+// of the lower one is removed by the mask anyway.  Written as asm because the compiler, knowing
+// those bits are dead, splits a 64-bit shift back into two 32-bit ones.
+__device__ __forceinline__ uint64_t shift_pair(uint32_t lo, uint32_t hi)
+{
+    uint64_t v = (static_cast<uint64_t>(hi) << 32) | lo;
+    asm("v_lshrrev_b64 %0, 4, %0" : "+v"(v));
+    return v;
+}
+
+__device__ __forceinline__ v4i high_codes(const v4u &p)
+{
+    const uint64_t lo = shift_pair(p[0], p[1]);
+    const uint64_t hi = shift_pair(p[2], p[3]);
+    v4i r;
+    r[0] = static_cast<int>(static_cast<uint32_t>(lo) & kLowNibbles);
+    r[1] = static_cast<int>(static_cast<uint32_t>(lo >> 32) & kLowNibbles);
+    r[2] = static_cast<int>(static_cast<uint32_t>(hi) & kLowNibbles);
+    r[3] = static_cast<int>(static_cast<uint32_t>(hi >> 32) & kLowNibbles);
+    return r;
+}
 
 // Workgroup id -> output tile.  Consecutive workgroup ids land on different XCDs (each with
 // its own L2), so ids are first regrouped so that one XCD owns a contiguous run of tiles,
@@ -621,22 +642,41 @@ q4_gemm_direct_kernel(const KernelArgs p)
         b_off[i] = static_cast<uint32_t>(n * p.ldb + c * 16);
         b_lim[i] = p.kbytes - c * 16;
     }
-    const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(p.A, p.a_bytes);
-    const __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(p.B, p.b_bytes);
 
-    typedef __attribute__((address_space(3))) void *lds_ptr;
+    // The loads are written as asm on purpose.  Through the builtin the compiler knows they write
+    // LDS, cannot tell that they never touch the ring slot being read, and puts s_waitcnt vmcnt(0)
+    // in front of the next LDS read: the whole HBM latency, every step (measured: ~1000 of ~2700
+    // cycles per step).  Which slot is written and when it may be read is the ring discipline
+    // below, enforced by the explicit vmcnt wait in front of each barrier.
+    auto descriptor = [](const void *base, uint32_t bytes) {  // same words as make_rsrc
+        const uint64_t b = reinterpret_cast<uint64_t>(base);
+        v4i d;
+        d[0] = __builtin_amdgcn_readfirstlane(static_cast<int>(b & 0xFFFFFFFFu));
+        d[1] = __builtin_amdgcn_readfirstlane(static_cast<int>((b >> 32) & 0xFFFFu));
+        d[2] = __builtin_amdgcn_readfirstlane(static_cast<int>(bytes));
+        d[3] = 0x00020000;
+        return d;
+    };
+    const v4i a_desc = descriptor(p.A, p.a_bytes), b_desc = descriptor(p.B, p.b_bytes);
+    auto lds_address = [&](const uint4 *ptr) {
+        return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void *)ptr));
+    };
+    auto load_to_lds = [&](const v4i &desc, uint32_t voffset, int soffset, uint32_t lds_byte) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :
+                     : "s"(lds_byte), "v"(voffset), "s"(desc), "s"(soffset)
+                     : "memory", "m0");
+    };
     auto issue = [&](int kt, int slot) {
         const int k0 = kt * kStepBytes;
 #pragma unroll
-        for (int i = 0; i < GA; ++i) {
-            uint4 *dst = &lds[slot][(wave + i * NW) * 16 * kChunks];
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr)dst, 16, k0 < a_lim[i] ? a_off[i] : kOutOfRange, k0, 0, 0);
-        }
+        for (int i = 0; i < GA; ++i)
+            load_to_lds(a_desc, k0 < a_lim[i] ? a_off[i] : kOutOfRange, k0,
+                        lds_address(&lds[slot][(wave + i * NW) * 16 * kChunks]));
 #pragma unroll
-        for (int i = 0; i < GB; ++i) {
-            uint4 *dst = &lds[slot][BM * kChunks + (wave + i * NW) * 16 * kChunks];
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr)dst, 16, k0 < b_lim[i] ? b_off[i] : kOutOfRange, k0, 0, 0);
-        }
+        for (int i = 0; i < GB; ++i)
+            load_to_lds(b_desc, k0 < b_lim[i] ? b_off[i] : kOutOfRange, k0,
+                        lds_address(&lds[slot][BM * kChunks + (wave + i * NW) * 16 * kChunks]));
     };
 
     // ---- LDS -> matrix cores: row (lane % 32) of each fragment, chunk 2*s + lane/32
@@ -681,11 +721,14 @@ q4_gemm_direct_kernel(const KernelArgs p)
     };
     auto widen_b = [&](int set, int first, int last) {  // dwords [first, last) of the set's B fragments
 #pragma unroll
-        for (int d = 0; d < 4 * FN; ++d) {
+        for (int d = 0; d < 4 * FN; d += 2) {  // [first, last) is a whole number of dword pairs
             if (d < first || d >= last) continue;
-            const uint32_t w = pb[set][d / 4][d % 4];
-            ub_lo[set][d / 4][d % 4] = static_cast<int>(w & kLowNibbles);
-            ub_hi[set][d / 4][d % 4] = static_cast<int>((w >> 4) & kLowNibbles);
+            const uint32_t w0 = pb[set][d / 4][d % 4], w1 = pb[set][d / 4][d % 4 + 1];
+            const uint64_t sh = shift_pair(w0, w1);
+            ub_lo[set][d / 4][d % 4] = static_cast<int>(w0 & kLowNibbles);
+            ub_lo[set][d / 4][d % 4 + 1] = static_cast<int>(w1 & kLowNibbles);
+            ub_hi[set][d / 4][d % 4] = static_cast<int>(static_cast<uint32_t>(sh) & kLowNibbles);
+            ub_hi[set][d / 4][d % 4 + 1] = static_cast<int>(static_cast<uint32_t>(sh >> 32) & kLowNibbles);
         }
     };
     auto half_step = [&](const int set, const int slot_next) {
@@ -736,6 +779,7 @@ q4_gemm_direct_kernel(const KernelArgs p)
 
     // ---- epilogue: add the zero-point terms of Eq. (2) and store
     store_tile<BM, FM, FN>(acc, terms, p, m0 + wm * WM, n0 + wn * WN, wm * WM, wn * WN, lane);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the zero-fill loads issued past the last step
 #endif
 }
 
