@@ -667,16 +667,25 @@ q4_gemm_direct_kernel(const KernelArgs p)
                      : "s"(lds_byte), "v"(voffset), "s"(desc), "s"(soffset)
                      : "memory", "m0");
     };
-    auto issue = [&](int kt, int slot) {
+    // Load number j (0 .. GA + GB - 1) of depth step kt into ring slot `slot`.  The loads of a step
+    // are spread over the fragment rows of the main loop: issued back to back by all eight waves
+    // they queue up in the address path and stall the waves (and their products) behind them.
+    auto issue_one = [&](int kt, int slot, int j) {
         const int k0 = kt * kStepBytes;
 #pragma unroll
         for (int i = 0; i < GA; ++i)
-            load_to_lds(a_desc, k0 < a_lim[i] ? a_off[i] : kOutOfRange, k0,
-                        lds_address(&lds[slot][(wave + i * NW) * 16 * kChunks]));
+            if (j == i)
+                load_to_lds(a_desc, k0 < a_lim[i] ? a_off[i] : kOutOfRange, k0,
+                            lds_address(&lds[slot][(wave + i * NW) * 16 * kChunks]));
 #pragma unroll
         for (int i = 0; i < GB; ++i)
-            load_to_lds(b_desc, k0 < b_lim[i] ? b_off[i] : kOutOfRange, k0,
-                        lds_address(&lds[slot][BM * kChunks + (wave + i * NW) * 16 * kChunks]));
+            if (j == GA + i)
+                load_to_lds(b_desc, k0 < b_lim[i] ? b_off[i] : kOutOfRange, k0,
+                            lds_address(&lds[slot][BM * kChunks + (wave + i * NW) * 16 * kChunks]));
+    };
+    auto issue = [&](int kt, int slot) {
+#pragma unroll
+        for (int j = 0; j < kLoadsPerStep; ++j) issue_one(kt, slot, j);
     };
 
     // ---- LDS -> matrix cores: row (lane % 32) of each fragment, chunk 2*s + lane/32
@@ -731,7 +740,8 @@ q4_gemm_direct_kernel(const KernelArgs p)
             ub_hi[set][d / 4][d % 4 + 1] = static_cast<int>(static_cast<uint32_t>(sh >> 32) & kLowNibbles);
         }
     };
-    auto half_step = [&](const int set, const int slot_next) {
+    constexpr int kLoadsPerRow = (kLoadsPerStep + 2 * FM - 1) / (2 * FM);
+    auto half_step = [&](const int set, const int slot_next, const int kt_load, const int slot_load) {
         const int other = set ^ 1;
         read_b(slot_next, set, set);  // this parity's B was widened during the previous half-step
         __builtin_amdgcn_sched_barrier(0);
@@ -747,6 +757,8 @@ q4_gemm_direct_kernel(const KernelArgs p)
             ua_hi = high_codes(next_a);
             widen_b(other, i * 4 * FN / FM, (i + 1) * 4 * FN / FM);
             read_a(slot_next, set, set, i);  // fragment i of this set was widened one row ago
+#pragma unroll
+            for (int l = 0; l < kLoadsPerRow; ++l) issue_one(kt_load, slot_load, (set * FM + i) * kLoadsPerRow + l);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -770,9 +782,8 @@ q4_gemm_direct_kernel(const KernelArgs p)
     int cur = 0;
     for (int kt = 0; kt < steps; ++kt) {
         const int nxt = (cur == STAGES - 1) ? 0 : cur + 1;
-        issue(kt + STAGES, cur);
-        half_step(0, nxt);
-        half_step(1, nxt);
+        half_step(0, nxt, kt + STAGES, cur);
+        half_step(1, nxt, kt + STAGES, cur);
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((STAGES - 2) * kLoadsPerStep) : "memory");
         cur = nxt;
     }
