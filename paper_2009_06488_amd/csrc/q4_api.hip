@@ -135,8 +135,7 @@ int q4_gemm(int M, int N, int K,
             return Q4_ERR_HIP;
         B_nk = copy;
     }
-    if (q4::launch_rowsum(A, M, K, lda_bytes, rowsumA, s) != hipSuccess) return Q4_ERR_HIP;
-    if (q4::launch_rowsum(B_nk, N, K, ldb_nk, colsumB, s) != hipSuccess) return Q4_ERR_HIP;
+    if (q4::launch_rowsum2(A, M, lda_bytes, rowsumA, B_nk, N, ldb_nk, colsumB, K, s) != hipSuccess) return Q4_ERR_HIP;
 
     q4::GemmProblem p{};
     p.M = M;

@@ -181,14 +181,24 @@ repack_kn_to_nk_fast_kernel(const uint8_t *__restrict__ src, int K, int N, long 
 
 // ---------------------------------------------------------------- depth sums
 // LANES lanes cooperate on one row; a wave holds 64 / LANES rows.
+// A second matrix of the same depth (rows2 > 0) is summed in the same launch: q4_gemm needs the
+// sums of A and of B and one launch costs less than two.
 template <int LANES>
 __global__ void __launch_bounds__(256)
-rowsum_kernel(const uint8_t *__restrict__ A, int rows, int k, long ld, int32_t *__restrict__ sums)
+rowsum_kernel(const uint8_t *__restrict__ A, int rows, int k, long ld, int32_t *__restrict__ sums,
+              const uint8_t *__restrict__ A2, int rows2, long ld2, int32_t *__restrict__ sums2)
 {
     const int rowbytes = (k + 1) >> 1;
     const int ndw = (rowbytes + 3) >> 2;
     const int sub = threadIdx.x % LANES;
-    const long r = (blockIdx.x * 256L + threadIdx.x) / LANES;
+    long r = (blockIdx.x * 256L + threadIdx.x) / LANES;
+    if (r >= rows) {  // rows of the second matrix follow those of the first
+        r -= rows;
+        A = A2;
+        rows = rows2;
+        ld = ld2;
+        sums = sums2;
+    }
     int s = 0;
     if (r < rows) {
         const uint8_t *row = A + r * ld;
@@ -448,17 +458,24 @@ hipError_t launch_repack_kn_to_nk(const uint8_t *B_kn, int K, int N, int ldb,
     return hipGetLastError();
 }
 
-hipError_t launch_rowsum(const uint8_t *A, int rows, int k, long ld, int32_t *sums, hipStream_t stream)
+hipError_t launch_rowsum2(const uint8_t *A, int rows, long ld, int32_t *sums,
+                          const uint8_t *A2, int rows2, long ld2, int32_t *sums2, int k, hipStream_t stream)
 {
     const int rowbytes = (k + 1) >> 1;
+    const long total = static_cast<long>(rows) + rows2;
     if (rowbytes >= 1024) {
-        rowsum_kernel<64><<<grid_for(static_cast<long>(rows) * 64), 256, 0, stream>>>(A, rows, k, ld, sums);
+        rowsum_kernel<64><<<grid_for(total * 64), 256, 0, stream>>>(A, rows, k, ld, sums, A2, rows2, ld2, sums2);
     } else if (rowbytes >= 128) {
-        rowsum_kernel<16><<<grid_for(static_cast<long>(rows) * 16), 256, 0, stream>>>(A, rows, k, ld, sums);
+        rowsum_kernel<16><<<grid_for(total * 16), 256, 0, stream>>>(A, rows, k, ld, sums, A2, rows2, ld2, sums2);
     } else {
-        rowsum_kernel<4><<<grid_for(static_cast<long>(rows) * 4), 256, 0, stream>>>(A, rows, k, ld, sums);
+        rowsum_kernel<4><<<grid_for(total * 4), 256, 0, stream>>>(A, rows, k, ld, sums, A2, rows2, ld2, sums2);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_rowsum(const uint8_t *A, int rows, int k, long ld, int32_t *sums, hipStream_t stream)
+{
+    return launch_rowsum2(A, rows, ld, sums, nullptr, 0, 0, nullptr, k, stream);
 }
 
 bool conv_small_depth_applies(const ConvGeom &g, int OC)

@@ -49,6 +49,9 @@ hipError_t launch_pack(const uint8_t *src, int rows, int cols, int ld_src, int t
 hipError_t launch_repack_kn_to_nk(const uint8_t *B_kn, int K, int N, int ldb,
                                   uint8_t *B_nk, int ld_out, hipStream_t stream);
 hipError_t launch_rowsum(const uint8_t *A, int rows, int k, long ld, int32_t *sums, hipStream_t stream);
+// Sums of two matrices of the same depth in one launch.
+hipError_t launch_rowsum2(const uint8_t *A, int rows, long ld, int32_t *sums,
+                          const uint8_t *A2, int rows2, long ld2, int32_t *sums2, int k, hipStream_t stream);
 // Direct evaluation for depths KH*KW*C <= 32: no depth sums, no matrix cores.
 bool conv_small_depth_applies(const ConvGeom &g, int OC);
 hipError_t launch_conv_small_depth(const uint8_t *x, const uint8_t *w, const ConvGeom &g, int OC, int zw,
