@@ -187,3 +187,35 @@ def config5(M: int = 8192, N: int = 8192, K: int = 8192, seed: int = 5000) -> Pa
     a = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
     b = rng.integers(0, 256, size=(K, N // 2), dtype=np.uint8)
     return PackedGemmCase(f"cfg5_{M}x{N}x{K}", M, N, K, 7, 8, seed, a, b)
+
+
+# The paper's own OCR network (Table 2): six valid convolutions on a 25 x 33 grayscale input,
+# (filters, kernel, stride) per layer, ReLU after each (expressed as qmin = zo in the re-quantization).
+PAPER_CNN_LAYERS = ((8, 5, 1), (8, 3, 1), (8, 3, 2), (16, 3, 1), (16, 3, 2), (24, 3, 1))
+PAPER_CNN_SHIFTS = (19, 19, 18, 18, 19, 19)
+
+
+@dataclass
+class PaperCnnLayer:
+    cin: int
+    cout: int
+    k: int
+    stride: int
+    zw: int
+    mult: int
+    shift: int
+    zo: int
+    w_codes: np.ndarray = None   # cout x k x k x cin
+
+
+def paper_cnn(batch: int = 8, seed: int = 4100):
+    """Random-weight instance of the paper's topology; returns (x_codes batch x 25 x 33 x 1, zx, layers)."""
+    rng = np.random.default_rng(seed)
+    x = _codes(rng, (batch, 25, 33, 1))
+    layers, cin = [], 1
+    for (cout, k, stride), shift in zip(PAPER_CNN_LAYERS, PAPER_CNN_SHIFTS):
+        w = _codes(rng, (cout, k, k, cin))
+        mult = int(rng.integers(2 ** 14, 2 ** 15))
+        layers.append(PaperCnnLayer(cin, cout, k, stride, zw=8, mult=mult, shift=shift, zo=4, w_codes=w))
+        cin = cout
+    return x, 7, layers

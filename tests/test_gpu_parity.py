@@ -382,6 +382,39 @@ def test_cnn_config4_full_batch_sampled_images():
         assert np.array_equal(got[img * per:(img + 1) * per], want), img
 
 
+def test_paper_cnn_topology():
+    """The paper's own network (Table 2: 25x33 input, 5x5 then 3x3 valid convolutions, two of them with
+    stride 2, ReLU as qmin = zo), random weights: unfused and fused GPU forward against the oracle."""
+    say("paper CNN topology")
+    x, zx0, layers = wl.paper_cnn(batch=8)
+    N = x.shape[0]
+
+    def forward(conv, requant, pack_in):
+        H, W, cin, zx = 25, 33, 1, zx0
+        act = pack_in(flat_pack(x))
+        for L in layers:
+            w = pack_in(o.pack(L.w_codes.reshape(L.cout, -1)))
+            act = requant(conv(act, zx, w, L, N, H, W, cin), L)
+            H, W = (H - L.k) // L.stride + 1, (W - L.k) // L.stride + 1
+            zx, cin = L.zo, L.cout
+        return act, (H, W, cin)
+
+    want, shape = forward(
+        lambda a, zx, w, L, N, H, W, c: o.conv2d(a, zx, w, L.zw, N, H, W, c, L.k, L.k, (L.stride, L.stride), (0, 0), L.cout),
+        lambda y, L: o.requant(y, L.mult, L.shift, L.zo, L.zo, 15).reshape(-1), lambda a: a)
+    assert shape == (1, 3, 24)
+
+    def desc(L, N, H, W, c):
+        return q4.conv_desc(N, H, W, c, L.k, L.k, (L.stride, L.stride), (0, 0), L.cout)
+
+    got, _ = forward(lambda a, zx, w, L, N, H, W, c: q4.q4_conv2d_im2col(desc(L, N, H, W, c), a, zx, w, L.zw),
+                     lambda y, L: q4.q4_requant(y, L.mult, L.shift, L.zo, L.zo, 15).reshape(-1), dev)
+    assert np.array_equal(host(got), want)
+    fused, _ = forward(lambda a, zx, w, L, N, H, W, c: q4.q4_conv2d_requant(desc(L, N, H, W, c), a, zx, w, L.zw, L.mult, L.shift, L.zo, L.zo, 15),
+                       lambda y, L: y.reshape(-1), dev)
+    assert np.array_equal(host(fused), want)
+
+
 # ------------------------------------------------------------------ config 5: the large GEMM
 def test_gemm_config5_full_size():
     """8192^3 in the configuration the benchmark times.  Every element is compared with the BLAS
