@@ -130,7 +130,8 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u4 codes widened to i8, i32 accumulate",
+        "dtype": "int8",
+        "dtype_note": "uint4 codes widened to int8 MFMA operands, exact int32 accumulation",
         "data": "synthetic",
         "config": {"workload": f"config 5: uint4 GEMM M=N=K={S}, B given K x N packed, za=7 zb=8, int32 out",
                    "M": M, "N": N, "K": K, "step": "q4_gemm(Q4_B_KN): repack B + depth sums + MFMA product + epilogue"},
@@ -199,6 +200,27 @@ def _extras(q4, wl, torch, np, dev):
     """Secondary workloads (conv layer + re-quantization; the OCR-style CNN), GPU time only.
     Inputs are packed with q4_pack; parity of all of these is covered by tests/."""
     ex = {}
+
+    # memory-bound helpers at the size of the large GEMM: algorithmic bytes / time
+    S = 8192
+    codes = torch.randint(0, 16, (S, S), dtype=torch.uint8, device=dev)
+    packed = torch.empty((S, S // 2), dtype=torch.uint8, device=dev)
+    ms = _time_ms(lambda: q4.q4_pack(codes, out=packed), torch)
+    ex["pack_8192x8192_GBps"] = round(1.5 * S * S / (ms * 1e-3) / 1e9, 1)
+    sums = torch.empty(S, dtype=torch.int32, device=dev)
+    ms = _time_ms(lambda: q4.q4_rowsum(packed, S, out=sums), torch)
+    ex["rowsum_8192x8192_GBps"] = round(0.5 * S * S / (ms * 1e-3) / 1e9, 1)
+    tr = torch.empty_like(packed)
+    ms = _time_ms(lambda: q4.q4_repack_kn_to_nk(packed, S, S, out=tr), torch)
+    ex["repack_8192x8192_GBps"] = round(1.0 * S * S / (ms * 1e-3) / 1e9, 1)
+    acc = torch.randint(-400000, 400000, (S, S), dtype=torch.int32, device=dev)
+    ms = _time_ms(lambda: q4.q4_requant(acc, 24576, 20, 8, out=packed), torch)
+    ex["requant_8192x8192_GBps"] = round(4.5 * S * S / (ms * 1e-3) / 1e9, 1)
+    pooled = torch.empty(S * S // 8, dtype=torch.uint8, device=dev)
+    # the 32 MiB of `packed` seen as an NHWC tensor of 64 x 64 x 32 x 512 codes (= 8192 * 8192)
+    ms = _time_ms(lambda: q4.q4_maxpool2x2(packed.reshape(-1), 64, 64, 32, 512, out=pooled), torch)
+    ex["maxpool_64x64x32x512_GBps"] = round(0.625 * S * S / (ms * 1e-3) / 1e9, 1)
+    del codes, packed, sums, tr, acc, pooled
 
     def flat_pack(codes):
         t = torch.from_numpy(np.ascontiguousarray(codes).reshape(1, -1)).to(dev)

@@ -121,7 +121,7 @@ def q4_pack(src: torch.Tensor, transpose: bool = False, out: Optional[torch.Tens
     orows, ocols = (cols, rows) if transpose else (rows, cols)
     if out is None:
         out = torch.empty((orows, (ocols + 1) // 2), dtype=torch.uint8, device=src.device)
-    assert out.shape[0] == orows and out.stride(1) == 1
+    assert out.shape[0] == orows and out.stride(1) == 1 and out.shape[1] >= (ocols + 1) // 2
     _check(lib.q4_pack(_dev(src, torch.uint8), rows, cols, src.stride(0), int(transpose),
                        _dev(out, torch.uint8), out.stride(0), _stream()), "q4_pack")
     return out
@@ -131,6 +131,7 @@ def q4_rowsum(A: torch.Tensor, k: int, out: Optional[torch.Tensor] = None) -> to
     assert A.dim() == 2 and A.stride(1) == 1
     if out is None:
         out = torch.empty(A.shape[0], dtype=torch.int32, device=A.device)
+    assert A.shape[1] >= (k + 1) // 2 and out.numel() >= A.shape[0] and out.is_contiguous()
     _check(lib.q4_rowsum(_dev(A, torch.uint8), A.shape[0], k, A.stride(0), _dev(out, torch.int32), _stream()),
            "q4_rowsum")
     return out
@@ -140,9 +141,19 @@ def q4_repack_kn_to_nk(B_kn: torch.Tensor, K: int, N: int, out: Optional[torch.T
     assert B_kn.dim() == 2 and B_kn.stride(1) == 1
     if out is None:
         out = torch.empty((N, (K + 1) // 2), dtype=torch.uint8, device=B_kn.device)
+    assert B_kn.shape[0] >= K and B_kn.shape[1] >= (N + 1) // 2
+    assert out.dim() == 2 and out.stride(1) == 1 and out.shape[0] >= N and out.shape[1] >= (K + 1) // 2
     _check(lib.q4_repack_kn_to_nk(_dev(B_kn, torch.uint8), K, N, B_kn.stride(0),
                                   _dev(out, torch.uint8), out.stride(0), _stream()), "q4_repack_kn_to_nk")
     return out
+
+
+def _gemm_shapes(A, B_nk, out, M, N, K):
+    """The library cannot see buffer sizes; the binding can, and refuses calls that would run past them."""
+    assert A.shape[0] >= M and A.shape[1] >= (K + 1) // 2, "A is smaller than M x ceil(K/2)"
+    if B_nk is not None:
+        assert B_nk.shape[0] >= N and B_nk.shape[1] >= (K + 1) // 2, "B is smaller than N x ceil(K/2)"
+    assert out.dim() == 2 and out.stride(1) == 1 and out.shape[0] >= M and out.shape[1] >= N, "C is smaller than M x N"
 
 
 def q4_gemm(A: torch.Tensor, za: int, B: torch.Tensor, zb: int, M: int, N: int, K: int,
@@ -155,6 +166,9 @@ def q4_gemm(A: torch.Tensor, za: int, B: torch.Tensor, zb: int, M: int, N: int, 
     need = gemm_workspace_bytes(M, N, K, b_layout)
     if workspace is None:
         workspace = _workspace(need, A.device)
+    _gemm_shapes(A, B if b_layout == B_NK else None, out, M, N, K)
+    if b_layout == B_KN:
+        assert B.shape[0] >= K and B.shape[1] >= (N + 1) // 2
     _check(lib.q4_gemm(M, N, K, _dev(A, torch.uint8), A.stride(0), za,
                        _dev(B, torch.uint8), B.stride(0), zb, b_layout,
                        _dev(out, torch.int32), out.stride(0),
@@ -169,6 +183,8 @@ def q4_gemm_presummed(A: torch.Tensor, za: int, rowsumA: torch.Tensor, B_nk: tor
     assert A.dim() == 2 and B_nk.dim() == 2 and A.stride(1) == 1 and B_nk.stride(1) == 1
     if out is None:
         out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _gemm_shapes(A, B_nk, out, M, N, K)
+    assert rowsumA.numel() >= M and colsumB.numel() >= N and rowsumA.is_contiguous() and colsumB.is_contiguous()
     _check(lib.q4_gemm_presummed(M, N, K, _dev(A, torch.uint8), A.stride(0), za, _dev(rowsumA, torch.int32),
                                  _dev(B_nk, torch.uint8), B_nk.stride(0), zb, _dev(colsumB, torch.int32),
                                  _dev(out, torch.int32), out.stride(0), _stream()), "q4_gemm_presummed")
@@ -183,6 +199,13 @@ def conv_out_hw(d: ConvDesc) -> Tuple[int, int]:
     return ((d.H + 2 * d.pad_h - d.KH) // d.stride_h + 1, (d.W + 2 * d.pad_w - d.KW) // d.stride_w + 1)
 
 
+def _conv_shapes(desc, x, w, w_colsum):
+    depth = desc.KH * desc.KW * desc.C
+    assert 2 * x.numel() >= desc.N * desc.H * desc.W * desc.C, "x holds fewer than N*H*W*C codes"
+    assert w.numel() >= desc.OC * ((depth + 1) // 2), "w is smaller than OC x ceil(KH*KW*C/2)"
+    assert w_colsum is None or (w_colsum.numel() >= desc.OC and w_colsum.is_contiguous())
+
+
 def q4_conv2d_im2col(desc: ConvDesc, x: torch.Tensor, zx: int, w: torch.Tensor, zw: int,
                      w_colsum: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
                      workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
@@ -191,7 +214,8 @@ def q4_conv2d_im2col(desc: ConvDesc, x: torch.Tensor, zx: int, w: torch.Tensor, 
     OH, OW = conv_out_hw(desc)
     if out is None:
         out = torch.empty((desc.N * OH * OW, desc.OC), dtype=torch.int32, device=x.device)
-    assert out.is_contiguous()
+    assert out.is_contiguous() and out.numel() >= desc.N * OH * OW * desc.OC
+    _conv_shapes(desc, x, w, w_colsum)
     need = conv2d_workspace_bytes(desc)
     if workspace is None:
         workspace = _workspace(need, x.device)
@@ -211,7 +235,8 @@ def q4_conv2d_requant(desc: ConvDesc, x: torch.Tensor, zx: int, w: torch.Tensor,
     OH, OW = conv_out_hw(desc)
     if out is None:
         out = torch.empty((desc.N * OH * OW, (desc.OC + 1) // 2), dtype=torch.uint8, device=x.device)
-    assert out.is_contiguous()
+    assert out.is_contiguous() and out.numel() >= desc.N * OH * OW * ((desc.OC + 1) // 2)
+    _conv_shapes(desc, x, w, w_colsum)
     if workspace is None:
         workspace = _workspace(conv2d_workspace_bytes(desc), x.device)
     cs = _dev(w_colsum, torch.int32) if w_colsum is not None else None
@@ -228,7 +253,7 @@ def q4_requant(acc: torch.Tensor, mult: int, shift: int, zo: int, qmin: int = 0,
     rows, cols = acc.shape
     if out is None:
         out = torch.empty((rows, (cols + 1) // 2), dtype=torch.uint8, device=acc.device)
-    assert out.stride(1) == 1
+    assert out.dim() == 2 and out.stride(1) == 1 and out.shape[0] >= rows and out.shape[1] >= (cols + 1) // 2
     _check(lib.q4_requant(_dev(acc, torch.int32), rows, cols, acc.stride(0), mult, shift, zo, qmin, qmax,
                           _dev(out, torch.uint8), out.stride(0), _stream()), "q4_requant")
     return out
@@ -240,6 +265,8 @@ def q4_maxpool2x2(x: torch.Tensor, N: int, H: int, W: int, C: int,
     assert x.is_contiguous()
     if out is None:
         out = torch.empty((N * (H // 2) * (W // 2) * C + 1) // 2, dtype=torch.uint8, device=x.device)
+    assert 2 * x.numel() >= N * H * W * C, "x holds fewer than N*H*W*C codes"
+    assert out.is_contiguous() and 2 * out.numel() >= N * (H // 2) * (W // 2) * C
     _check(lib.q4_maxpool2x2(_dev(x, torch.uint8), N, H, W, C, _dev(out, torch.uint8), _stream()),
            "q4_maxpool2x2")
     return out

@@ -99,3 +99,17 @@ def test_other_argument_errors():
     assert L.q4_conv2d_requant(ref, FAKE, 0, FAKE, 0, None, 1, 20, 8, 0, 15, None, FAKE, 1 << 20, None) == q4.ERR_NULL
     bad = q4.conv_desc(1, 8, 8, 4, 3, 3, (0, 1), (1, 1), 4)
     assert L.q4_conv2d_im2col(ctypes.byref(bad), FAKE, 0, FAKE, 0, None, FAKE, FAKE, 1 << 20, None) == q4.ERR_SHAPE
+
+
+def test_binding_refuses_undersized_buffers():
+    """The C ABI cannot see buffer sizes; the binding checks them before any pointer reaches the library."""
+    import torch
+    small = torch.zeros(1024, dtype=torch.uint8)
+    with pytest.raises(AssertionError):
+        q4.q4_maxpool2x2(small, 64, 512, 256, 512)
+    with pytest.raises(AssertionError):
+        q4.q4_gemm(small.reshape(32, 32), 0, small.reshape(32, 32), 0, 64, 32, 64, q4.B_NK)
+    with pytest.raises(AssertionError):
+        q4.q4_conv2d_im2col(q4.conv_desc(1, 64, 64, 32, 3, 3, (1, 1), (1, 1), 64), small, 0, small, 0)
+    with pytest.raises(AssertionError):
+        q4.q4_rowsum(small.reshape(32, 32), 100)
