@@ -264,10 +264,12 @@ conv_small_depth_kernel(const uint8_t *__restrict__ x, const uint8_t *__restrict
     const long m = m_block + threadIdx.x;
     const bool active = m < M;
     const long mm = active ? m : M - 1;
-    const int ow = static_cast<int>(mm % g.OW);
-    const long t = mm / g.OW;
-    const int oh = static_cast<int>(t % g.OH);
-    const long pixel0 = (t / g.OH) * g.H * g.W;
+    const uint32_t mu = static_cast<uint32_t>(mm);  // M < 2^31: 32-bit divisions
+    const uint32_t t = mu / static_cast<uint32_t>(g.OW);
+    const int ow = static_cast<int>(mu - t * static_cast<uint32_t>(g.OW));
+    const uint32_t nimg = t / static_cast<uint32_t>(g.OH);
+    const int oh = static_cast<int>(t - nimg * static_cast<uint32_t>(g.OH));
+    const long pixel0 = static_cast<long>(nimg) * g.H * g.W;
     const bool vec_store = (OC % 4 == 0) && (reinterpret_cast<uintptr_t>(y) % 16 == 0);
     for (int oc0 = 0; oc0 < OC; oc0 += kOcGroup) {
         int acc[kOcGroup];

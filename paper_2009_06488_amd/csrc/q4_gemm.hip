@@ -103,11 +103,14 @@ struct PatchOrigin {
 
 __device__ __forceinline__ PatchOrigin patch_origin(const ConvGeom &g, long m)
 {
+    // m < 2^31 (checked by the host): 32-bit divisions, a fraction of the cost of 64-bit ones
     PatchOrigin o;
-    const int ow = static_cast<int>(m % g.OW);
-    const long t = m / g.OW;
-    const int oh = static_cast<int>(t % g.OH);
-    o.pixel0 = (t / g.OH) * g.H * g.W;
+    const uint32_t mu = static_cast<uint32_t>(m);
+    const uint32_t t = mu / static_cast<uint32_t>(g.OW);
+    const int ow = static_cast<int>(mu - t * static_cast<uint32_t>(g.OW));
+    const uint32_t n = t / static_cast<uint32_t>(g.OH);
+    const int oh = static_cast<int>(t - n * static_cast<uint32_t>(g.OH));
+    o.pixel0 = static_cast<long>(n) * g.H * g.W;
     o.ih0 = oh * g.sh - g.ph;
     o.iw0 = ow * g.sw - g.pw;
     return o;
@@ -428,7 +431,7 @@ q4_gemm_kernel(const KernelArgs p)
     int a_sum[NA];  // convolution: running sum of the codes this thread has gathered for each of its rows
 #pragma unroll
     for (int i = 0; i < NA; ++i) a_sum[i] = 0;
-    auto fetch = [&](int kt) {
+    auto fetch = [&](int kt, v4u (&a_reg)[NA], v4u (&b_reg)[NB]) {
         const int k0 = kt * kStepBytes;
         const int kb = k0 + chunk * 16;
         const bool present = k0 < chunk_limit;
@@ -474,7 +477,7 @@ q4_gemm_kernel(const KernelArgs p)
                 b_reg[i] = as_v4u(load_dense_chunk_generic(b_row[i], kb, p.kbytes, odd_k));
         }
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int buf, const v4u (&a_reg)[NA], const v4u (&b_reg)[NB]) {
         v4u *dst = reinterpret_cast<v4u *>(lds[buf]);
 #pragma unroll
         for (int i = 0; i < NA; ++i) dst[a_lds[i]] = a_reg[i];
@@ -509,11 +512,14 @@ q4_gemm_kernel(const KernelArgs p)
     // flight in registers while step kt is multiplied, and the packed fragments of the next
     // half-step are read from LDS while the matrix cores work on the current one.
     const int steps = (p.kbytes + kStepBytes - 1) / kStepBytes;
-    fetch(0);
-    stash(0);
-    fetch(1);
-    stash(1);
-    fetch(2);
+    {   // the first three steps are requested together: one HBM round trip instead of three
+        v4u a0[NA], b0[NB], a1[NA], b1[NB];
+        fetch(0, a0, b0);
+        fetch(1, a1, b1);
+        fetch(2, a_reg, b_reg);
+        stash(0, a0, b0);
+        stash(1, a1, b1);
+    }
     block_barrier();
 
     v4u pa[2][FM], pb[2][FN];
@@ -549,8 +555,8 @@ q4_gemm_kernel(const KernelArgs p)
         const int nxt2 = (nxt == kStages - 1) ? 0 : nxt + 1;
         // Past the last step the loaders return zeros and the ring slots written or pre-read are
         // ones nobody uses any more, so nothing below needs a branch.
-        stash(nxt2);
-        fetch(kt + 3);
+        stash(nxt2, a_reg, b_reg);
+        fetch(kt + 3, a_reg, b_reg);
         read_frags(cur, 1, 1);
         __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads ahead of the products they overlap with
         multiply(0);
