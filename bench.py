@@ -249,16 +249,18 @@ def _extras(q4, wl, torch, np, dev):
     case = wl.config4()
     act0 = flat_pack(case.x_codes)
     weights = [q4.q4_pack(torch.from_numpy(L.w_codes.reshape(L.cout, -1)).to(dev)) for L in case.layers]
+    # per-layer weight sums are part of the stored layer (computed once, Sec. 3.2 of the paper)
+    wsums = [q4.q4_rowsum(wt, 9 * L.cin) for L, wt in zip(case.layers, weights)]
 
     def cnn_step(fused=False):
         act, zx, cin, H, W = act0, case.zx, 1, case.H, case.W
-        for L, wt in zip(case.layers, weights):
+        for L, wt, ws_ in zip(case.layers, weights, wsums):
             dd = q4.conv_desc(case.batch, H, W, cin, 3, 3, (1, 1), (case.pad, case.pad), L.cout)
             H, W = q4.conv_out_hw(dd)
             if fused:
-                act = q4.q4_conv2d_requant(dd, act, zx, wt, L.zw, L.mult, L.shift, L.zo).reshape(-1)
+                act = q4.q4_conv2d_requant(dd, act, zx, wt, L.zw, L.mult, L.shift, L.zo, w_colsum=ws_).reshape(-1)
             else:
-                yy = q4.q4_conv2d_im2col(dd, act, zx, wt, L.zw)
+                yy = q4.q4_conv2d_im2col(dd, act, zx, wt, L.zw, w_colsum=ws_)
                 act = q4.q4_requant(yy, L.mult, L.shift, L.zo).reshape(-1)
             zx, cin = L.zo, L.cout
             if L.pool_after:
