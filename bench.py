@@ -220,7 +220,12 @@ def _extras(q4, wl, torch, np, dev):
     # the 32 MiB of `packed` seen as an NHWC tensor of 64 x 64 x 32 x 512 codes (= 8192 * 8192)
     ms = _time_ms(lambda: q4.q4_maxpool2x2(packed.reshape(-1), 64, 64, 32, 512, out=pooled), torch)
     ex["maxpool_64x64x32x512_GBps"] = round(0.625 * S * S / (ms * 1e-3) / 1e9, 1)
-    del codes, packed, sums, tr, acc, pooled
+    xf = torch.randn(S * S, dtype=torch.float32, device=dev)
+    ms = _time_ms(lambda: q4.q4_quantize_f32(xf), torch)
+    ex["quantize_f32_64M_GBps"] = round(4.5 * S * S / (ms * 1e-3) / 1e9, 1)
+    ms = _time_ms(lambda: q4.q4_dequant_f32(acc.reshape(-1), 0.01, out=xf), torch)
+    ex["dequant_f32_64M_GBps"] = round(8.0 * S * S / (ms * 1e-3) / 1e9, 1)
+    del codes, packed, sums, tr, acc, pooled, xf
 
     def flat_pack(codes):
         t = torch.from_numpy(np.ascontiguousarray(codes).reshape(1, -1)).to(dev)

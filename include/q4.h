@@ -190,6 +190,28 @@ int q4_requant(const int32_t *acc, long rows, int cols, long ld_acc,
                uint8_t *out, long ld_out_bytes, void *stream);
 
 /*
+ * q4_quantize_f32 -- float activations to 4-bit codes: the F -> Q transition of
+ * Sec. 3.2 with the linear quantizer of Eq. (1), p = 4, in the code-unit
+ * convention that Eq. (2) builds on (real = scale * (code - zero)):
+ *   scale = (max(max x, 0) - min(min x, 0)) / 15,  zero = -floor(min(min x, 0) / scale),
+ *   code  = clamp(floor(x / scale) + zero, 0, 15);   all-zero x gives scale 1, zero 0.
+ * Every step is one float32 operation in that order.
+ *   x     : n floats.          out : ceil(n/2) bytes of packed codes.
+ *   scale : one float, zero : one int32, both DEVICE memory written by the call
+ *           (read them after synchronising, or pass them on to later kernels).
+ *   workspace : >= q4_quantize_workspace_bytes() bytes, 16-byte aligned.
+ */
+size_t q4_quantize_workspace_bytes(void);
+int q4_quantize_f32(const float *x, long n, float *scale, int32_t *zero, uint8_t *out,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * q4_dequant_f32 -- the Q -> F transition (Eq. (4)): out[i] = scale * acc[i], where
+ * scale is the product of the scales of the two quantized operands.
+ */
+int q4_dequant_f32(const int32_t *acc, long n, float scale, float *out, void *stream);
+
+/*
  * q4_maxpool2x2 -- 2x2 max-pool with stride 2 on packed NHWC codes (valid on
  * codes because q4_requant is monotone).  C must be even; odd H or W drop the
  * last row / column.  y is N x (H/2) x (W/2) x C, packed.

@@ -245,6 +245,49 @@ long q4o_max_channels(int64_t acc_max, int q_bits, long kh, long kw)
     return d < 0 ? d : d / (kh * kw);
 }
 
+/*
+ * Float boundary of a mixed network (Sec. 3.2, F -> Q and Q -> F transitions).
+ *
+ * Quantizer of Eq. (1) with p = 4, in the code-unit convention that Eq. (2) builds on
+ * (real = s * (code - z)):
+ *     s = (max(max x, 0) - min(min x, 0)) / 15,   z = -floor(min(min x, 0) / s),
+ *     code = clamp(floor(x / s) + z, 0, 15).
+ * An all-zero input gives s = 1, z = 0.  The decisions (floor of a quotient) are taken in
+ * float32, the precision of the GPU kernel they are compared with; every operation is a single
+ * IEEE float32 operation, written in the order above.
+ */
+int q4o_quantize_f32(const float *x, long n, float *scale, int *zero, uint8_t *packed)
+{
+    if (!x || !scale || !zero || !packed || n <= 0) return Q4O_ERR_ARG;
+    float lo = 0.0f, hi = 0.0f;
+    for (long i = 0; i < n; ++i) {
+        if (x[i] < lo) lo = x[i];
+        if (x[i] > hi) hi = x[i];
+    }
+    float s = (hi - lo) / 15.0f;
+    int z = 0;
+    if (s > 0.0f) z = -(int)__builtin_floorf(lo / s);
+    else s = 1.0f;
+    for (long b = 0; b < (n + 1) / 2; ++b) packed[b] = 0;
+    for (long i = 0; i < n; ++i) {
+        int q = (int)__builtin_floorf(x[i] / s) + z;
+        if (q < 0) q = 0;
+        if (q > 15) q = 15;
+        packed[i >> 1] |= (uint8_t)(q << (4 * (int)(i & 1)));
+    }
+    *scale = s;
+    *zero = z;
+    return Q4O_OK;
+}
+
+/* Q -> F (Eq. (4)): r = s * r_hat, one float32 multiplication of the converted integer. */
+int q4o_dequant_f32(const int32_t *acc, long n, float scale, float *out)
+{
+    if (!acc || !out || n <= 0) return Q4O_ERR_ARG;
+    for (long i = 0; i < n; ++i) out[i] = scale * (float)acc[i];
+    return Q4O_OK;
+}
+
 /* Number of OpenMP threads the loops above will use (1 without OpenMP). */
 #ifdef _OPENMP
 #include <omp.h>

@@ -66,6 +66,8 @@ def _load():
         lib.q4o_max_depth.restype = L
         lib.q4o_max_channels.argtypes = [ctypes.c_int64, I, L, L]
         lib.q4o_max_channels.restype = L
+        lib.q4o_quantize_f32.argtypes = [P, L, P, P, P]
+        lib.q4o_dequant_f32.argtypes = [P, L, ctypes.c_float, P]
         lib.q4o_threads.restype = I
         lib.q4o_set_threads.argtypes = [I]
         lib.q4o_set_threads.restype = None
@@ -214,3 +216,21 @@ def max_depth(acc_max: int, q_bits: int) -> int:
 
 def max_channels(acc_max: int, q_bits: int, kh: int, kw: int) -> int:
     return int(_load().q4o_max_channels(acc_max, q_bits, kh, kw))
+
+
+def quantize_f32(x):
+    """Eq. (1) quantizer (float32 decisions): returns (packed codes, scale, zero point)."""
+    x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    packed = np.empty((x.size + 1) // 2, dtype=np.uint8)
+    s = np.zeros(1, dtype=np.float32)
+    z = np.zeros(1, dtype=np.int32)
+    _check(_load().q4o_quantize_f32(_ptr(x), x.size, _ptr(s), _ptr(z), _ptr(packed)), "quantize_f32")
+    return packed, float(s[0]), int(z[0])
+
+
+def dequant_f32(acc, scale: float) -> np.ndarray:
+    """Eq. (4): float32 scale times the integer result."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    out = np.empty(acc.shape, dtype=np.float32)
+    _check(_load().q4o_dequant_f32(_ptr(acc), acc.size, scale, _ptr(out)), "dequant_f32")
+    return out

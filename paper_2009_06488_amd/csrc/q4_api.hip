@@ -293,6 +293,28 @@ int q4_requant(const int32_t *acc, long rows, int cols, long ld_acc,
                                     static_cast<hipStream_t>(stream)));
 }
 
+size_t q4_quantize_workspace_bytes(void) { return q4::quantize_workspace_bytes(); }
+
+int q4_quantize_f32(const float *x, long n, float *scale, int32_t *zero, uint8_t *out,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x || !scale || !zero || !out) return Q4_ERR_NULL;
+    if (n <= 0) return Q4_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(x) % 4 || reinterpret_cast<uintptr_t>(scale) % 4 || reinterpret_cast<uintptr_t>(zero) % 4)
+        return Q4_ERR_ALIGN;
+    if (!workspace || workspace_bytes < q4_quantize_workspace_bytes()) return Q4_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16) return Q4_ERR_ALIGN;
+    return rc_of(q4::launch_quantize_f32(x, n, scale, zero, out, workspace, static_cast<hipStream_t>(stream)));
+}
+
+int q4_dequant_f32(const int32_t *acc, long n, float scale, float *out, void *stream)
+{
+    if (!acc || !out) return Q4_ERR_NULL;
+    if (n <= 0) return Q4_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(acc) % 4 || reinterpret_cast<uintptr_t>(out) % 4) return Q4_ERR_ALIGN;
+    return rc_of(q4::launch_dequant_f32(acc, n, scale, out, static_cast<hipStream_t>(stream)));
+}
+
 int q4_maxpool2x2(const uint8_t *x, int N, int H, int W, int C, uint8_t *y, void *stream)
 {
     if (!x || !y) return Q4_ERR_NULL;

@@ -380,6 +380,89 @@ requant_generic_kernel(const int32_t *__restrict__ acc, long rows, int cols, lon
     }
 }
 
+
+// ---------------------------------------------------------------- float boundary (F -> Q, Q -> F)
+// Quantizer of Eq. (1) of the paper with p = 4, in the code-unit convention of Eq. (2):
+//   s = (max(max x, 0) - min(min x, 0)) / 15,  z = -floor(min(min x, 0) / s),
+//   code = clamp(floor(x / s) + z, 0, 15).
+// Pass 1 leaves one (min, max) pair per block in the workspace; every block of pass 2 folds those
+// pairs again (they are few), derives s and z with single float32 operations in the order above
+// and quantizes its share of x.
+constexpr int kMinMaxBlocks = 1024;
+
+__device__ __forceinline__ void block_minmax(float &lo, float &hi, float (*sh)[2])
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, off, 64));
+        hi = fmaxf(hi, __shfl_xor(hi, off, 64));
+    }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+        sh[wave][0] = lo;
+        sh[wave][1] = hi;
+    }
+    __syncthreads();
+    lo = fminf(fminf(sh[0][0], sh[1][0]), fminf(sh[2][0], sh[3][0]));
+    hi = fmaxf(fmaxf(sh[0][1], sh[1][1]), fmaxf(sh[2][1], sh[3][1]));
+    __syncthreads();
+}
+
+__global__ void __launch_bounds__(256)
+minmax_partial_kernel(const float *__restrict__ x, long n, float2 *__restrict__ partial)
+{
+    __shared__ float sh[4][2];
+    float lo = 0.0f, hi = 0.0f;  // the range of Eq. (1) always contains zero
+    for (long i = blockIdx.x * 256L + threadIdx.x; i < n; i += 256L * gridDim.x) {
+        const float v = x[i];
+        lo = fminf(lo, v);
+        hi = fmaxf(hi, v);
+    }
+    block_minmax(lo, hi, sh);
+    if (threadIdx.x == 0) partial[blockIdx.x] = make_float2(lo, hi);
+}
+
+__global__ void __launch_bounds__(256)
+quantize_f32_kernel(const float *__restrict__ x, long n, const float2 *__restrict__ partial, int n_partial,
+                    float *__restrict__ scale, int32_t *__restrict__ zero, uint8_t *__restrict__ out)
+{
+    __shared__ float sh[4][2];
+    float lo = 0.0f, hi = 0.0f;
+    for (int i = threadIdx.x; i < n_partial; i += 256) {
+        const float2 p = partial[i];
+        lo = fminf(lo, p.x);
+        hi = fmaxf(hi, p.y);
+    }
+    block_minmax(lo, hi, sh);
+    float s = (hi - lo) / 15.0f;
+    int z = 0;
+    if (s > 0.0f) z = -static_cast<int>(floorf(lo / s));
+    else s = 1.0f;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *scale = s;
+        *zero = z;
+    }
+    const long n_bytes = (n + 1) >> 1;
+    for (long b = blockIdx.x * 256L + threadIdx.x; b < n_bytes; b += 256L * gridDim.x) {
+        int q0 = static_cast<int>(floorf(x[2 * b] / s)) + z;
+        q0 = min(max(q0, 0), 15);
+        int q1 = 0;
+        if (2 * b + 1 < n) {
+            q1 = static_cast<int>(floorf(x[2 * b + 1] / s)) + z;
+            q1 = min(max(q1, 0), 15);
+        }
+        out[b] = static_cast<uint8_t>(q0 | (q1 << 4));
+    }
+}
+
+// Q -> F, Eq. (4): r = s * r_hat.
+__global__ void __launch_bounds__(256)
+dequant_f32_kernel(const int32_t *__restrict__ acc, long n, float scale, float *__restrict__ out)
+{
+    for (long i = blockIdx.x * 256L + threadIdx.x; i < n; i += 256L * gridDim.x)
+        out[i] = scale * static_cast<float>(acc[i]);
+}
+
 // ---------------------------------------------------------------- 2x2 max-pool
 // Per-nibble maximum of two packed words (nibbles split into two byte lanes each < 16,
 // so the borrow-free SWAR compare below is exact).
@@ -509,6 +592,24 @@ hipError_t launch_requant(const int32_t *acc, long rows, int cols, long ld_acc,
         requant_generic_kernel<<<grid_for(rows * ((cols + 1) / 2), 256, 1 << 16), 256, 0, stream>>>(
             acc, rows, cols, ld_acc, mult, shift, zo, qmin, qmax, out, ld_out);
     }
+    return hipGetLastError();
+}
+
+size_t quantize_workspace_bytes() { return kMinMaxBlocks * sizeof(float2); }
+
+hipError_t launch_quantize_f32(const float *x, long n, float *scale, int32_t *zero, uint8_t *out,
+                               void *workspace, hipStream_t stream)
+{
+    float2 *partial = static_cast<float2 *>(workspace);
+    const int blocks = grid_for(n, 256 * 8, kMinMaxBlocks);
+    minmax_partial_kernel<<<blocks, 256, 0, stream>>>(x, n, partial);
+    quantize_f32_kernel<<<grid_for((n + 1) / 2, 256, 1 << 16), 256, 0, stream>>>(x, n, partial, blocks, scale, zero, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequant_f32(const int32_t *acc, long n, float scale, float *out, hipStream_t stream)
+{
+    dequant_f32_kernel<<<grid_for(n, 256 * 4, 1 << 16), 256, 0, stream>>>(acc, n, scale, out);
     return hipGetLastError();
 }
 

@@ -59,6 +59,11 @@ hipError_t launch_conv_small_depth(const uint8_t *x, const uint8_t *w, const Con
 hipError_t launch_requant(const int32_t *acc, long rows, int cols, long ld_acc,
                           int32_t mult, int shift, int zo, int qmin, int qmax,
                           uint8_t *out, long ld_out, hipStream_t stream);
+// Float boundary: Eq. (1) quantizer (min/max pass + quantize pass) and Eq. (4) dequantization.
+size_t quantize_workspace_bytes();
+hipError_t launch_quantize_f32(const float *x, long n, float *scale, int32_t *zero, uint8_t *out,
+                               void *workspace, hipStream_t stream);
+hipError_t launch_dequant_f32(const int32_t *acc, long n, float scale, float *out, hipStream_t stream);
 hipError_t launch_maxpool2x2(const uint8_t *x, int N, int H, int W, int C, uint8_t *y, hipStream_t stream);
 
 }  // namespace q4

@@ -25,6 +25,7 @@ EXPORTS = (
     "q4_version", "q4_strerror", "q4_max_depth", "q4_pack", "q4_rowsum", "q4_repack_kn_to_nk",
     "q4_gemm_workspace_bytes", "q4_gemm", "q4_gemm_presummed", "q4_conv2d_workspace_bytes", "q4_conv2d_im2col", "q4_conv2d_requant",
     "q4_requant", "q4_maxpool2x2", "q4_debug_force_tile",
+    "q4_quantize_workspace_bytes", "q4_quantize_f32", "q4_dequant_f32",
 )
 
 
@@ -63,6 +64,9 @@ def _load() -> ctypes.CDLL:
     lib.q4_conv2d_requant.argtypes = [ctypes.POINTER(ConvDesc), P, I, P, I, P, ctypes.c_int32, I, I, I, I, P, P, Z, P]
     lib.q4_requant.argtypes = [P, L, I, L, ctypes.c_int32, I, I, I, I, P, L, P]
     lib.q4_maxpool2x2.argtypes = [P, I, I, I, I, P, P]
+    lib.q4_quantize_workspace_bytes.restype = Z
+    lib.q4_quantize_f32.argtypes = [P, L, P, P, P, P, Z, P]
+    lib.q4_dequant_f32.argtypes = [P, L, ctypes.c_float, P, P]
     lib.q4_debug_force_tile.argtypes = [I]
     lib.q4_debug_force_tile.restype = None
     return lib
@@ -269,4 +273,28 @@ def q4_maxpool2x2(x: torch.Tensor, N: int, H: int, W: int, C: int,
     assert out.is_contiguous() and 2 * out.numel() >= N * (H // 2) * (W // 2) * C
     _check(lib.q4_maxpool2x2(_dev(x, torch.uint8), N, H, W, C, _dev(out, torch.uint8), _stream()),
            "q4_maxpool2x2")
+    return out
+
+
+def q4_quantize_f32(x: torch.Tensor):
+    """Float tensor -> (packed codes, scale tensor (1 float), zero-point tensor (1 int32)), all on the device."""
+    assert x.is_contiguous()
+    n = x.numel()
+    out = torch.empty((n + 1) // 2, dtype=torch.uint8, device=x.device)
+    scale = torch.empty(1, dtype=torch.float32, device=x.device)
+    zero = torch.empty(1, dtype=torch.int32, device=x.device)
+    ws = _workspace(int(lib.q4_quantize_workspace_bytes()), x.device)
+    _check(lib.q4_quantize_f32(_dev(x, torch.float32), n, _dev(scale, torch.float32), _dev(zero, torch.int32),
+                               _dev(out, torch.uint8), _dev(ws, torch.uint8), ws.numel(), _stream()), "q4_quantize_f32")
+    return out, scale, zero
+
+
+def q4_dequant_f32(acc: torch.Tensor, scale: float, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """int32 tensor -> float32 tensor scale * acc."""
+    assert acc.is_contiguous()
+    if out is None:
+        out = torch.empty(acc.shape, dtype=torch.float32, device=acc.device)
+    assert out.is_contiguous() and out.numel() >= acc.numel()
+    _check(lib.q4_dequant_f32(_dev(acc, torch.int32), acc.numel(), float(scale), _dev(out, torch.float32), _stream()),
+           "q4_dequant_f32")
     return out

@@ -101,6 +101,17 @@ def test_other_argument_errors():
     assert L.q4_conv2d_im2col(ctypes.byref(bad), FAKE, 0, FAKE, 0, None, FAKE, FAKE, 1 << 20, None) == q4.ERR_SHAPE
 
 
+def test_float_boundary_argument_errors():
+    L = q4.lib
+    assert q4.lib.q4_quantize_workspace_bytes() == 8192
+    assert L.q4_quantize_f32(None, 4, FAKE, FAKE, FAKE, FAKE, 1 << 20, None) == q4.ERR_NULL
+    assert L.q4_quantize_f32(FAKE, 0, FAKE, FAKE, FAKE, FAKE, 1 << 20, None) == q4.ERR_SHAPE
+    assert L.q4_quantize_f32(FAKE, 4, FAKE, FAKE, FAKE, FAKE, 16, None) == q4.ERR_WORKSPACE
+    assert L.q4_quantize_f32(FAKE + 2, 4, FAKE, FAKE, FAKE, FAKE, 1 << 20, None) == q4.ERR_ALIGN
+    assert L.q4_dequant_f32(FAKE, 4, 1.0, None, None) == q4.ERR_NULL
+    assert L.q4_dequant_f32(FAKE, -1, 1.0, FAKE, None) == q4.ERR_SHAPE
+
+
 def test_binding_refuses_undersized_buffers():
     """The C ABI cannot see buffer sizes; the binding checks them before any pointer reaches the library."""
     import torch

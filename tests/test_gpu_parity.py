@@ -382,6 +382,28 @@ def test_cnn_config4_full_batch_sampled_images():
         assert np.array_equal(got[img * per:(img + 1) * per], want), img
 
 
+@pytest.mark.parametrize("n,lo,hi", [(1, -1.0, 1.0), (7, 0.5, 9.0), (1001, -3.0, 5.0), (4096, -7.0, -1.0),
+                                     (300001, -2.5, 2.5), (2 ** 22 + 3, -1e-3, 2e-3)])
+def test_quantize_and_dequant_f32(n, lo, hi):
+    """F -> Q (Eq. (1)) and Q -> F (Eq. (4)): codes, scale and zero point must equal the oracle's, whose
+    decisions are taken in float32 like the kernel's."""
+    say("quantize_f32", n, lo, hi)
+    rng = np.random.default_rng(n)
+    x = rng.uniform(lo, hi, size=n).astype(np.float32)
+    x[0] = 0.0
+    want, s, z = o.quantize_f32(x)
+    got, gs, gz = q4.q4_quantize_f32(dev(x))
+    assert float(host(gs)[0]) == s and int(host(gz)[0]) == z
+    assert np.array_equal(host(got), want)
+    acc = rng.integers(-2 ** 31, 2 ** 31, size=min(n, 5000), dtype=np.int64).astype(np.int32)
+    assert np.array_equal(host(q4.q4_dequant_f32(dev(acc), s * 0.37)), o.dequant_f32(acc, np.float32(s * 0.37)))
+
+
+def test_quantize_all_zero():
+    got, gs, gz = q4.q4_quantize_f32(dev(np.zeros(9, np.float32)))
+    assert float(host(gs)[0]) == 1.0 and int(host(gz)[0]) == 0 and not host(got).any()
+
+
 def test_paper_cnn_topology():
     """The paper's own network (Table 2: 25x33 input, 5x5 then 3x3 valid convolutions, two of them with
     stride 2, ReLU as qmin = zo), random weights: unfused and fused GPU forward against the oracle."""

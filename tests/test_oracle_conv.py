@@ -122,3 +122,41 @@ def test_requant_monotone_and_in_range():
     relu = o.unpack_rows(o.requant(np.maximum(acc, 0), 30000, 18, 8), 1, acc.size)
     clamp = o.unpack_rows(o.requant(acc, 30000, 18, 8, qmin=8), 1, acc.size)
     assert np.array_equal(relu, clamp)
+
+
+def test_quantizer_handworked(golden):
+    g = golden("handworked.txt")
+    for key in ("quant_a", "quant_b"):
+        s, z, codes = g[key]
+        packed, gs, gz = o.quantize_f32(np.array(g[key + "_x"], dtype=np.float32))
+        assert (gs, gz) == (s, z)
+        assert o.unpack(packed, len(codes)).tolist() == codes
+
+
+def test_quantizer_properties():
+    """Eq. (1): zero maps to the zero point; codes cover 0..15; s * (code - z) brackets x within one step;
+    a NumPy float32 restatement gives the same codes; all-zero input is handled."""
+    rng = np.random.default_rng(8)
+    for lo, hi in ((-3.0, 5.0), (0.5, 9.0), (-7.0, -1.0), (-1e-3, 2e-3)):
+        x = rng.uniform(lo, hi, size=1001).astype(np.float32)
+        x[0] = 0.0
+        packed, s, z = o.quantize_f32(x)
+        q = o.unpack(packed, x.size).astype(np.int64)
+        assert 0 <= z <= 15 and q[0] == z
+        assert q.min() == 0 and q.max() == 15
+        lo0, hi0 = np.float32(min(x.min(), 0)), np.float32(max(x.max(), 0))
+        s32 = np.float32((hi0 - lo0) / np.float32(15))
+        assert s == float(s32) and z == -int(np.floor(lo0 / s32))
+        ref = np.clip(np.floor(x / s32).astype(np.int64) + z, 0, 15)
+        assert np.array_equal(q, ref)
+        real = s * (q - z).astype(np.float64)
+        inner = (q > 0) & (q < 15)
+        assert np.all(real[inner] <= x[inner] + 1e-6 * abs(hi - lo)) and np.all(x[inner] < real[inner] + s * (1 + 1e-5))
+    packed, s, z = o.quantize_f32(np.zeros(7, np.float32))
+    assert (s, z) == (1.0, 0) and not packed.any()
+
+
+def test_dequant():
+    acc = np.array([0, 1, -3, 1843200, -2 ** 31], dtype=np.int32)
+    out = o.dequant_f32(acc, 0.125)
+    assert out.dtype == np.float32 and out.tolist() == [0.0, 0.125, -0.375, 230400.0, -268435456.0]
