@@ -156,6 +156,19 @@ def main():
         },
     }
 
+    # ---- the paper's comparison: the same product with 8-bit codes (one per byte), same kernel minus the split
+    if not args.no_extras:
+        g8 = torch.Generator(device=dev)
+        g8.manual_seed(5008)
+        A8 = torch.randint(0, 256, (M, K), dtype=torch.uint8, device=dev, generator=g8)
+        B8 = torch.randint(0, 256, (N, K), dtype=torch.uint8, device=dev, generator=g8)
+        ws8 = torch.empty(int(q4.lib.q8_gemm_workspace_bytes(M, N)), dtype=torch.uint8, device=dev)
+        ms8 = _time_ms(lambda: q4.q8_gemm(A8, 128, B8, 128, M, N, K, out=C2, workspace=ws8), torch, reps=50, warm=10)
+        out["extras"]["q8_gemm_ms"] = round(ms8, 4)
+        out["extras"]["q8_gemm_tops"] = round(ops / (ms8 * 1e-3) / 1e12, 2)
+        out["extras"]["speedup_4bit_over_8bit_nk_calls"] = round(ms8 / nk_ms, 3)
+        del A8, B8, ws8
+
     if not args.no_cpu_baseline:
         from oracle import q4_oracle as o
         rng = np.random.default_rng(7)

@@ -190,6 +190,24 @@ int q4_requant(const int32_t *acc, long rows, int cols, long ld_acc,
                uint8_t *out, long ld_out_bytes, void *stream);
 
 /*
+ * q8_gemm -- the 8-bit sibling of q4_gemm, the case the paper compares against
+ * (Sec. 2.2: unsigned 8-bit codes, 32-bit accumulators; Sec. 4.1):
+ *   C[m*ldc + n] = sum_{k<K} (A[m,k] - za) * (B[k,n] - zb), exact int32.
+ * Same kernel as the 4-bit path without the nibble split.  Restricted to what the
+ * comparison needs:
+ *   A : M rows of K bytes, B_nk : N rows of K bytes (one code per byte, 0..255),
+ *       both 16-byte aligned with row pitches that are multiples of 16; K % 16 == 0;
+ *       otherwise Q4_ERR_ALIGN.  0 <= za, zb <= 255.  K <= 32768 (Q4_ERR_OVERFLOW beyond).
+ *   workspace : >= q8_gemm_workspace_bytes(M, N) bytes, 16-byte aligned.
+ */
+size_t q8_gemm_workspace_bytes(int M, int N);
+int q8_gemm(int M, int N, int K,
+            const uint8_t *A, int lda_bytes, int za,
+            const uint8_t *B_nk, int ldb_bytes, int zb,
+            int32_t *C, int ldc,
+            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * q4_quantize_f32 -- float activations to 4-bit codes: the F -> Q transition of
  * Sec. 3.2 with the linear quantizer of Eq. (1), p = 4, in the code-unit
  * convention that Eq. (2) builds on (real = scale * (code - zero)):

@@ -246,6 +246,27 @@ long q4o_max_channels(int64_t acc_max, int q_bits, long kh, long kw)
 }
 
 /*
+ * 8-bit sibling (the paper's comparison case, Sec. 2.2: unsigned 8-bit codes, wide accumulators):
+ *   C[m, n] = sum_k (A[m, k] - za) * (B[n, k] - zb),  A: M x K bytes, B: N x K bytes, codes 0..255.
+ */
+int q8o_gemm(long M, long N, long K, const uint8_t *A, long lda, int za,
+             const uint8_t *B_nk, long ldb, int zb, int32_t *C, long ldc)
+{
+    if (!A || !B_nk || !C || M <= 0 || N <= 0 || K <= 0) return Q4O_ERR_ARG;
+    if (za < 0 || za > 255 || zb < 0 || zb > 255 || lda < K || ldb < K || ldc < N) return Q4O_ERR_ARG;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (long m = 0; m < M; ++m)
+        for (long n = 0; n < N; ++n) {
+            int64_t s = 0;
+            for (long k = 0; k < K; ++k) s += (int64_t)((int)A[m * lda + k] - za) * (int64_t)((int)B_nk[n * ldb + k] - zb);
+            if (s > INT32_MAX || s < INT32_MIN) bad = 1;
+            C[m * ldc + n] = (int32_t)s;
+        }
+    return bad ? Q4O_ERR_OVERFLOW : Q4O_OK;
+}
+
+/*
  * Float boundary of a mixed network (Sec. 3.2, F -> Q and Q -> F transitions).
  *
  * Quantizer of Eq. (1) with p = 4, in the code-unit convention that Eq. (2) builds on

@@ -66,6 +66,7 @@ def _load():
         lib.q4o_max_depth.restype = L
         lib.q4o_max_channels.argtypes = [ctypes.c_int64, I, L, L]
         lib.q4o_max_channels.restype = L
+        lib.q8o_gemm.argtypes = [L, L, L, P, L, I, P, L, I, P, L]
         lib.q4o_quantize_f32.argtypes = [P, L, P, P, P]
         lib.q4o_dequant_f32.argtypes = [P, L, ctypes.c_float, P]
         lib.q4o_threads.restype = I
@@ -234,3 +235,14 @@ def dequant_f32(acc, scale: float) -> np.ndarray:
     out = np.empty(acc.shape, dtype=np.float32)
     _check(_load().q4o_dequant_f32(_ptr(acc), acc.size, scale, _ptr(out)), "dequant_f32")
     return out
+
+
+def gemm8(A, za: int, B_nk, zb: int) -> np.ndarray:
+    """8-bit sibling: A (M x K bytes) times B_nk (N x K bytes) transposed, zero points 0..255; int32 M x N."""
+    A, B_nk = _u8(A), _u8(B_nk)
+    assert A.ndim == 2 and B_nk.ndim == 2 and A.shape[1] == B_nk.shape[1]
+    M, K = A.shape
+    N = B_nk.shape[0]
+    C = np.empty((M, N), dtype=np.int32)
+    _check(_load().q8o_gemm(M, N, K, _ptr(A), K, za, _ptr(B_nk), K, zb, _ptr(C), N), "gemm8")
+    return C

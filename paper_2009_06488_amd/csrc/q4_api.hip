@@ -293,6 +293,51 @@ int q4_requant(const int32_t *acc, long rows, int cols, long ld_acc,
                                     static_cast<hipStream_t>(stream)));
 }
 
+size_t q8_gemm_workspace_bytes(int M, int N)
+{
+    if (M <= 0 || N <= 0) return 0;
+    return align_up(4 * (static_cast<size_t>(M) + static_cast<size_t>(N)), 16);
+}
+
+int q8_gemm(int M, int N, int K,
+            const uint8_t *A, int lda_bytes, int za,
+            const uint8_t *B_nk, int ldb_bytes, int zb,
+            int32_t *C, int ldc,
+            void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!A || !B_nk || !C) return Q4_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0) return Q4_ERR_SHAPE;
+    if (lda_bytes < K || ldb_bytes < K || ldc < N) return Q4_ERR_SHAPE;
+    if (za < 0 || za > 255 || zb < 0 || zb > 255) return Q4_ERR_RANGE;
+    if (K > 32768) return Q4_ERR_OVERFLOW;  // 255^2 * K must stay below 2^31
+    if (reinterpret_cast<uintptr_t>(C) % 4) return Q4_ERR_ALIGN;
+    if (K % 16 || lda_bytes % 16 || ldb_bytes % 16 || reinterpret_cast<uintptr_t>(A) % 16 ||
+        reinterpret_cast<uintptr_t>(B_nk) % 16)
+        return Q4_ERR_ALIGN;
+    if ((M - 1L) * lda_bytes + K >= 0xFFFFFF00L || (N - 1L) * ldb_bytes + K >= 0xFFFFFF00L) return Q4_ERR_SHAPE;
+    if (!workspace || workspace_bytes < q8_gemm_workspace_bytes(M, N)) return Q4_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16) return Q4_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t *rowsumA = static_cast<int32_t *>(workspace);
+    int32_t *colsumB = rowsumA + M;
+    if (q4::launch_rowsum8x2(A, M, lda_bytes, rowsumA, B_nk, N, ldb_bytes, colsumB, K, s) != hipSuccess) return Q4_ERR_HIP;
+    q4::GemmProblem p{};
+    p.M = M;
+    p.N = N;
+    p.K = K;
+    p.A = A;
+    p.lda = lda_bytes;
+    p.B = B_nk;
+    p.ldb = ldb_bytes;
+    p.C = C;
+    p.ldc = ldc;
+    p.rowsumA = rowsumA;
+    p.colsumB = colsumB;
+    p.za = za;
+    p.zb = zb;
+    return rc_of(q4::launch_gemm8(p, s));
+}
+
 size_t q4_quantize_workspace_bytes(void) { return q4::quantize_workspace_bytes(); }
 
 int q4_quantize_f32(const float *x, long n, float *scale, int32_t *zero, uint8_t *out,

@@ -236,6 +236,38 @@ __device__ __forceinline__ uint32_t requant_one(int32_t acc, int32_t mult, int s
     return static_cast<uint32_t>(q);
 }
 
+
+// Depth sums of 8-bit codes (sibling path): one wave per row, 16-byte loads, byte sums by v_sad_u8.
+__global__ void __launch_bounds__(256)
+rowsum8_kernel(const uint8_t *__restrict__ A, int rows, int k, long ld, int32_t *__restrict__ sums,
+               const uint8_t *__restrict__ A2, int rows2, long ld2, int32_t *__restrict__ sums2)
+{
+    const int lane = threadIdx.x & 63;
+    long r = blockIdx.x * 4L + (threadIdx.x >> 6);
+    if (r >= rows) {
+        r -= rows;
+        A = A2;
+        rows = rows2;
+        ld = ld2;
+        sums = sums2;
+    }
+    uint32_t s = 0;
+    if (r < rows) {
+        const uint4 *row = reinterpret_cast<const uint4 *>(A + r * ld);  // the launcher requires 16-byte rows
+        for (int i = lane; i < k / 16; i += 64) {
+            const uint4 v = row[i];
+            s = __builtin_amdgcn_sad_u8(v.x, 0u, s);
+            s = __builtin_amdgcn_sad_u8(v.y, 0u, s);
+            s = __builtin_amdgcn_sad_u8(v.z, 0u, s);
+            s = __builtin_amdgcn_sad_u8(v.w, 0u, s);
+        }
+    }
+    int t = static_cast<int>(s);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) t += __shfl_xor(t, off, 64);
+    if (r < rows && lane == 0) sums[r] = t;
+}
+
 // ---------------------------------------------------------------- small-depth convolution
 // For depths up to 32 codes (e.g. a 3x3 kernel on a single-channel image) the matrix cores have
 // nothing to chew on and the layer is bound by writing its int32 output.  One thread owns one
@@ -555,6 +587,14 @@ hipError_t launch_rowsum2(const uint8_t *A, int rows, long ld, int32_t *sums,
     } else {
         rowsum_kernel<4><<<grid_for(total * 4), 256, 0, stream>>>(A, rows, k, ld, sums, A2, rows2, ld2, sums2);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_rowsum8x2(const uint8_t *A, int rows, long ld, int32_t *sums,
+                            const uint8_t *A2, int rows2, long ld2, int32_t *sums2, int k, hipStream_t stream)
+{
+    const long total = static_cast<long>(rows) + rows2;
+    rowsum8_kernel<<<grid_for(total, 4), 256, 0, stream>>>(A, rows, k, ld, sums, A2, rows2, ld2, sums2);
     return hipGetLastError();
 }
 

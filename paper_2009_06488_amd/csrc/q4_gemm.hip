@@ -48,6 +48,8 @@ struct KernelArgs {
     uint32_t a_bytes, b_bytes;  // extent of A and B for range-checked loads (aligned modes)
     long lda, ldb, ldc;
     int za, zb;
+    int sum_bias;   // subtracted from every depth sum before use (8-bit path: 128 * K; 4-bit: 0)
+    int raw_bias;   // subtracted from every raw product sum (8-bit path: zero-filled depth tail)
     int tiles_m, tiles_n;
     int stagger_first, stagger_count;  // workgroups [first, first + count) start late by stagger_ticks
     int stagger_ticks;                 // in ticks of the 100 MHz wall clock
@@ -267,9 +269,9 @@ template <int BM, int BN, int T, bool ROWS = true>
 __device__ __forceinline__ void stage_terms(int *terms, const KernelArgs &p, int m0, int n0, int tid)
 {
     if constexpr (ROWS)
-        for (int r = tid; r < BM; r += T) terms[r] = (m0 + r < p.M) ? -p.zb * p.rowsumA[m0 + r] : 0;
-    const int kzz = p.K * p.za * p.zb;
-    for (int c = tid; c < BN; c += T) terms[BM + c] = (n0 + c < p.N) ? kzz - p.za * p.colsumB[n0 + c] : 0;
+        for (int r = tid; r < BM; r += T) terms[r] = (m0 + r < p.M) ? -p.zb * (p.rowsumA[m0 + r] - p.sum_bias) : 0;
+    const int kzz = p.K * p.za * p.zb - p.raw_bias;
+    for (int c = tid; c < BN; c += T) terms[BM + c] = (n0 + c < p.N) ? kzz - p.za * (p.colsumB[n0 + c] - p.sum_bias) : 0;
 }
 
 // In a 32x32 accumulator fragment register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4 and
@@ -598,7 +600,7 @@ q4_gemm_kernel(const KernelArgs p)
 // a ring of STAGES depth steps whose loads stay in flight across the per-step barrier.
 // A wave-wide load fills 64 consecutive 16-byte LDS slots (16 rows x 4 chunks); the XOR
 // swizzle is applied by choosing which chunk of global memory each lane fetches.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int BITS = 4>
 __global__ void __launch_bounds__(WAVES_M *WAVES_N * 64, (min_waves_per_simd(BM / WAVES_M, BN / WAVES_N)))
 q4_gemm_direct_kernel(const KernelArgs p)
 {
@@ -740,6 +742,11 @@ q4_gemm_direct_kernel(const KernelArgs p)
             if (d < first || d >= last) continue;
             const uint32_t w0 = pb[set][d / 4][d % 4], w1 = pb[set][d / 4][d % 4 + 1];
             const uint64_t sh = shift_pair(w0, w1);
+            if constexpr (BITS == 8) {  // unsigned 8-bit codes: code - 128 as a signed byte, nothing to split
+                ub_lo[set][d / 4][d % 4] = static_cast<int>(w0 ^ 0x80808080u);
+                ub_lo[set][d / 4][d % 4 + 1] = static_cast<int>(w1 ^ 0x80808080u);
+                continue;
+            }
             ub_lo[set][d / 4][d % 4] = static_cast<int>(w0 & kLowNibbles);
             ub_lo[set][d / 4][d % 4 + 1] = static_cast<int>(w1 & kLowNibbles);
             ub_hi[set][d / 4][d % 4] = static_cast<int>(static_cast<uint32_t>(sh) & kLowNibbles);
@@ -756,11 +763,17 @@ q4_gemm_direct_kernel(const KernelArgs p)
             const v4i alo = ua_lo, ahi = ua_hi;
 #pragma unroll
             for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo, ub_lo[set][j], acc[i][j], 0, 0, 0);
+            if constexpr (BITS == 4) {
 #pragma unroll
-            for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi, ub_hi[set][j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi, ub_hi[set][j], acc[i][j], 0, 0, 0);
+            }
             const v4u next_a = (i + 1 < FM) ? pa[set][(i + 1) % FM] : pa[other][0];
-            ua_lo = low_codes(next_a);
-            ua_hi = high_codes(next_a);
+            if constexpr (BITS == 8) {
+                ua_lo = (v4i)(next_a ^ 0x80808080u);
+            } else {
+                ua_lo = low_codes(next_a);
+                ua_hi = high_codes(next_a);
+            }
             widen_b(other, i * 4 * FN / FM, (i + 1) * 4 * FN / FM);
             read_a(slot_next, set, set, i);  // fragment i of this set was widened one row ago
 #pragma unroll
@@ -782,8 +795,13 @@ q4_gemm_direct_kernel(const KernelArgs p)
         for (int i = 0; i < FM; ++i) read_a(0, h, h, i);
     }
     widen_b(0, 0, 4 * FN);
-    ua_lo = low_codes(pa[0][0]);
-    ua_hi = high_codes(pa[0][0]);
+    if constexpr (BITS == 8) {
+        ua_lo = (v4i)(pa[0][0] ^ 0x80808080u);
+        ua_hi = ua_lo;
+    } else {
+        ua_lo = low_codes(pa[0][0]);
+        ua_hi = high_codes(pa[0][0]);
+    }
     block_barrier();  // every wave has taken step 0 out of its slot before the loop refills it
     int cur = 0;
     for (int kt = 0; kt < steps; ++kt) {
@@ -822,6 +840,8 @@ hipError_t launch_tile(const GemmProblem &q, hipStream_t stream)
     a.ldc = q.ldc;
     a.za = q.za;
     a.zb = q.zb;
+    a.sum_bias = 0;
+    a.raw_bias = 0;
     a.tiles_m = (q.M + BM - 1) / BM;
     a.tiles_n = (q.N + BN - 1) / BN;
     a.g = q.g;
@@ -870,7 +890,43 @@ hipError_t launch_tile(const GemmProblem &q, hipStream_t stream)
     return hipGetLastError();
 }
 
+// Eight-bit sibling (the paper's comparison case, Sec. 2.2: 8-bit codes, 32-bit accumulators): same
+// kernel without the nibble split.  Unsigned codes c become signed bytes c - 128 by flipping the top
+// bit; the zero points move by the same 128 and the depth sums by 128 * K, so Eq. (2) is unchanged.
+hipError_t launch_tile8(const GemmProblem &q, hipStream_t stream)
+{
+    constexpr int BM = 256, BN = 256;
+    KernelArgs a{};
+    a.A = q.A;
+    a.B = q.B;
+    a.C = q.C;
+    a.rowsumA = q.rowsumA;
+    a.colsumB = q.colsumB;
+    a.M = q.M;
+    a.N = q.N;
+    a.K = q.K;
+    a.kbytes = q.K;  // one byte per code
+    a.lda = q.lda;
+    a.ldb = q.ldb;
+    a.ldc = q.ldc;
+    a.za = q.za - 128;
+    a.zb = q.zb - 128;
+    a.sum_bias = 128 * q.K;
+    const int steps = (q.K + kStepBytes - 1) / kStepBytes;
+    a.raw_bias = (steps * kStepBytes - q.K) * 128 * 128;  // zero-filled tail bytes read as code 0 = -128 on both sides
+    a.tiles_m = (q.M + BM - 1) / BM;
+    a.tiles_n = (q.N + BN - 1) / BN;
+    a.a_bytes = static_cast<uint32_t>((q.M - 1L) * q.lda + q.K);
+    a.b_bytes = static_cast<uint32_t>((q.N - 1L) * q.ldb + q.K);
+    a.stagger_first = a.stagger_count = a.stagger_ticks = 0;
+    const dim3 grid(static_cast<unsigned>(a.tiles_m) * static_cast<unsigned>(a.tiles_n));
+    q4_gemm_direct_kernel<BM, BN, 2, 4, 4, 8><<<grid, dim3(512), 0, stream>>>(a);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_gemm8(const GemmProblem &p, hipStream_t stream) { return launch_tile8(p, stream); }
 
 hipError_t launch_gemm(const GemmProblem &p, int force_tile, hipStream_t stream)
 {

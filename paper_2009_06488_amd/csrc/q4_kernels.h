@@ -59,6 +59,10 @@ hipError_t launch_conv_small_depth(const uint8_t *x, const uint8_t *w, const Con
 hipError_t launch_requant(const int32_t *acc, long rows, int cols, long ld_acc,
                           int32_t mult, int shift, int zo, int qmin, int qmax,
                           uint8_t *out, long ld_out, hipStream_t stream);
+// Eight-bit sibling path: depth sums of two byte matrices in one launch, and the product.
+hipError_t launch_rowsum8x2(const uint8_t *A, int rows, long ld, int32_t *sums,
+                            const uint8_t *A2, int rows2, long ld2, int32_t *sums2, int k, hipStream_t stream);
+hipError_t launch_gemm8(const GemmProblem &p, hipStream_t stream);
 // Float boundary: Eq. (1) quantizer (min/max pass + quantize pass) and Eq. (4) dequantization.
 size_t quantize_workspace_bytes();
 hipError_t launch_quantize_f32(const float *x, long n, float *scale, int32_t *zero, uint8_t *out,

@@ -25,7 +25,7 @@ EXPORTS = (
     "q4_version", "q4_strerror", "q4_max_depth", "q4_pack", "q4_rowsum", "q4_repack_kn_to_nk",
     "q4_gemm_workspace_bytes", "q4_gemm", "q4_gemm_presummed", "q4_conv2d_workspace_bytes", "q4_conv2d_im2col", "q4_conv2d_requant",
     "q4_requant", "q4_maxpool2x2", "q4_debug_force_tile",
-    "q4_quantize_workspace_bytes", "q4_quantize_f32", "q4_dequant_f32",
+    "q4_quantize_workspace_bytes", "q4_quantize_f32", "q4_dequant_f32", "q8_gemm_workspace_bytes", "q8_gemm",
 )
 
 
@@ -67,6 +67,9 @@ def _load() -> ctypes.CDLL:
     lib.q4_quantize_workspace_bytes.restype = Z
     lib.q4_quantize_f32.argtypes = [P, L, P, P, P, P, Z, P]
     lib.q4_dequant_f32.argtypes = [P, L, ctypes.c_float, P, P]
+    lib.q8_gemm_workspace_bytes.argtypes = [I, I]
+    lib.q8_gemm_workspace_bytes.restype = Z
+    lib.q8_gemm.argtypes = [I, I, I, P, I, I, P, I, I, P, I, P, Z, P]
     lib.q4_debug_force_tile.argtypes = [I]
     lib.q4_debug_force_tile.restype = None
     return lib
@@ -297,4 +300,20 @@ def q4_dequant_f32(acc: torch.Tensor, scale: float, out: Optional[torch.Tensor] 
     assert out.is_contiguous() and out.numel() >= acc.numel()
     _check(lib.q4_dequant_f32(_dev(acc, torch.int32), acc.numel(), float(scale), _dev(out, torch.float32), _stream()),
            "q4_dequant_f32")
+    return out
+
+
+def q8_gemm(A: torch.Tensor, za: int, B_nk: torch.Tensor, zb: int, M: int, N: int, K: int,
+            out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """8-bit sibling: A M x K bytes, B_nk N x K bytes (one code per byte) -> int32 M x N."""
+    assert A.dim() == 2 and B_nk.dim() == 2 and A.stride(1) == 1 and B_nk.stride(1) == 1
+    assert A.shape[0] >= M and A.shape[1] >= K and B_nk.shape[0] >= N and B_nk.shape[1] >= K
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    assert out.dim() == 2 and out.stride(1) == 1 and out.shape[0] >= M and out.shape[1] >= N
+    if workspace is None:
+        workspace = _workspace(int(lib.q8_gemm_workspace_bytes(M, N)), A.device)
+    _check(lib.q8_gemm(M, N, K, _dev(A, torch.uint8), A.stride(0), za, _dev(B_nk, torch.uint8), B_nk.stride(0), zb,
+                       _dev(out, torch.int32), out.stride(0), _dev(workspace, torch.uint8), workspace.numel(),
+                       _stream()), "q8_gemm")
     return out

@@ -17,7 +17,7 @@ FAKE = 0x10000  # a non-NULL, 16-byte aligned address that is never dereferenced
 def _declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(q4_[a-z0-9_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(q[48]_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported():

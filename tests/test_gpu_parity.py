@@ -404,6 +404,22 @@ def test_quantize_all_zero():
     assert float(host(gs)[0]) == 1.0 and int(host(gz)[0]) == 0 and not host(got).any()
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 1, 16), (64, 32, 80), (257, 255, 96), (300, 200, 528), (1024, 1024, 1152), (70, 40, 32768)])
+def test_gemm8_sibling(M, N, K):
+    """8-bit sibling path (the paper's comparison case) against its oracle, incl. a depth tail and extremes."""
+    say("gemm8", M, N, K)
+    rng = np.random.default_rng(M + N + K)
+    za, zb = (int(v) for v in rng.integers(0, 256, size=2))
+    a = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+    b = rng.integers(0, 256, size=(N, K), dtype=np.uint8)
+    if K == 32768:
+        a[:] = 255
+        b[:] = 0
+        za, zb = 0, 255
+    got = host(q4.q8_gemm(dev(a), za, dev(b), zb, M, N, K))
+    assert np.array_equal(got, o.gemm8(a, za, b, zb))
+
+
 def test_paper_cnn_topology():
     """The paper's own network (Table 2: 25x33 input, 5x5 then 3x3 valid convolutions, two of them with
     stride 2, ReLU as qmin = zo), random weights: unfused and fused GPU forward against the oracle."""

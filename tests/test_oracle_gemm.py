@@ -133,3 +133,23 @@ def test_bad_arguments_are_rejected():
         o.gemm(a, 0, a, -1, 2, 2, 2)
     with pytest.raises(ValueError):
         o.gemm(a, 0, a, 0, 2, 2, 4)      # rows too short for K = 4
+
+
+def test_gemm8_pins():
+    """8-bit sibling: hand-worked value, NumPy int64 matmul, the four-term identity of Eq. (2), extremes."""
+    # hand-worked: A = [[200, 10]], B_nk = [[0, 255]], za = 100, zb = 5: (100)(-5) + (-90)(250) = -500 - 22500
+    assert o.gemm8(np.array([[200, 10]], np.uint8), 100, np.array([[0, 255]], np.uint8), 5).tolist() == [[-23000]]
+    rng = np.random.default_rng(21)
+    for M, N, K in ((3, 5, 7), (17, 9, 64), (33, 40, 200)):
+        za, zb = (int(v) for v in rng.integers(0, 256, size=2))
+        a = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        b = rng.integers(0, 256, size=(N, K), dtype=np.uint8)
+        got = o.gemm8(a, za, b, zb)
+        a64, b64 = a.astype(np.int64), b.astype(np.int64)
+        assert np.array_equal(got, (a64 - za) @ (b64 - zb).T)
+        four = a64 @ b64.T - za * b64.sum(1)[None, :] - zb * a64.sum(1)[:, None] + K * za * zb
+        assert np.array_equal(got, four)
+    K = 32768
+    full, zero = np.full((1, K), 255, np.uint8), np.zeros((1, K), np.uint8)
+    assert o.gemm8(full, 0, full, 0).tolist() == [[255 * 255 * K]]
+    assert o.gemm8(full, 0, zero, 255).tolist() == [[-255 * 255 * K]]
