@@ -445,10 +445,15 @@ minmax_partial_kernel(const float *__restrict__ x, long n, float2 *__restrict__ 
 {
     __shared__ float sh[4][2];
     float lo = 0.0f, hi = 0.0f;  // the range of Eq. (1) always contains zero
-    for (long i = blockIdx.x * 256L + threadIdx.x; i < n; i += 256L * gridDim.x) {
-        const float v = x[i];
-        lo = fminf(lo, v);
-        hi = fmaxf(hi, v);
+    const long n4 = (reinterpret_cast<uintptr_t>(x) % 16 == 0) ? n / 4 : 0;
+    for (long i = blockIdx.x * 256L + threadIdx.x; i < n4; i += 256L * gridDim.x) {
+        const float4 v = reinterpret_cast<const float4 *>(x)[i];
+        lo = fminf(fminf(lo, v.x), fminf(fminf(v.y, v.z), v.w));
+        hi = fmaxf(fmaxf(hi, v.x), fmaxf(fmaxf(v.y, v.z), v.w));
+    }
+    for (long i = 4 * n4 + blockIdx.x * 256L + threadIdx.x; i < n; i += 256L * gridDim.x) {
+        lo = fminf(lo, x[i]);
+        hi = fmaxf(hi, x[i]);
     }
     block_minmax(lo, hi, sh);
     if (threadIdx.x == 0) partial[blockIdx.x] = make_float2(lo, hi);
@@ -474,16 +479,23 @@ quantize_f32_kernel(const float *__restrict__ x, long n, const float2 *__restric
         *scale = s;
         *zero = z;
     }
+    auto code = [&](float v) {
+        const int q = static_cast<int>(floorf(v / s)) + z;
+        return static_cast<uint32_t>(min(max(q, 0), 15));
+    };
+    // eight floats (two 16-byte loads) -> one packed dword; the ragged tail goes byte by byte
+    const long n_groups = (reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 4 == 0) ? n / 8 : 0;
+    for (long g = blockIdx.x * 256L + threadIdx.x; g < n_groups; g += 256L * gridDim.x) {
+        const float4 v0 = reinterpret_cast<const float4 *>(x)[2 * g], v1 = reinterpret_cast<const float4 *>(x)[2 * g + 1];
+        const uint32_t w = code(v0.x) | code(v0.y) << 4 | code(v0.z) << 8 | code(v0.w) << 12 |
+                           code(v1.x) << 16 | code(v1.y) << 20 | code(v1.z) << 24 | code(v1.w) << 28;
+        reinterpret_cast<uint32_t *>(out)[g] = w;
+    }
     const long n_bytes = (n + 1) >> 1;
-    for (long b = blockIdx.x * 256L + threadIdx.x; b < n_bytes; b += 256L * gridDim.x) {
-        int q0 = static_cast<int>(floorf(x[2 * b] / s)) + z;
-        q0 = min(max(q0, 0), 15);
-        int q1 = 0;
-        if (2 * b + 1 < n) {
-            q1 = static_cast<int>(floorf(x[2 * b + 1] / s)) + z;
-            q1 = min(max(q1, 0), 15);
-        }
-        out[b] = static_cast<uint8_t>(q0 | (q1 << 4));
+    for (long b = 4 * n_groups + blockIdx.x * 256L + threadIdx.x; b < n_bytes; b += 256L * gridDim.x) {
+        uint32_t w = code(x[2 * b]);
+        if (2 * b + 1 < n) w |= code(x[2 * b + 1]) << 4;
+        out[b] = static_cast<uint8_t>(w);
     }
 }
 
@@ -643,7 +655,7 @@ hipError_t launch_quantize_f32(const float *x, long n, float *scale, int32_t *ze
     float2 *partial = static_cast<float2 *>(workspace);
     const int blocks = grid_for(n, 256 * 8, kMinMaxBlocks);
     minmax_partial_kernel<<<blocks, 256, 0, stream>>>(x, n, partial);
-    quantize_f32_kernel<<<grid_for((n + 1) / 2, 256, 1 << 16), 256, 0, stream>>>(x, n, partial, blocks, scale, zero, out);
+    quantize_f32_kernel<<<grid_for((n + 7) / 8, 256, 1 << 16), 256, 0, stream>>>(x, n, partial, blocks, scale, zero, out);
     return hipGetLastError();
 }
 
