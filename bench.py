@@ -244,6 +244,15 @@ def _extras(q4, wl, torch, np, dev):
         t = torch.from_numpy(np.ascontiguousarray(codes).reshape(1, -1)).to(dev)
         return q4.q4_pack(t).reshape(-1)
 
+    # configs 1 and 2: small GEMMs (launch / latency bound), whole q4_gemm call with B given K x N
+    for (M_, N_, K_) in ((64, 32, 72), (64, 64, 72), (256, 256, 288), (1024, 1024, 1152), (1024, 64, 1152)):
+        a_ = torch.randint(0, 256, (M_, K_ // 2), dtype=torch.uint8, device=dev)
+        b_ = torch.randint(0, 256, (K_, N_ // 2), dtype=torch.uint8, device=dev)
+        c_ = torch.empty((M_, N_), dtype=torch.int32, device=dev)
+        w_ = torch.empty(q4.gemm_workspace_bytes(M_, N_, K_, q4.B_KN), dtype=torch.uint8, device=dev)
+        ms = _time_ms(lambda: q4.q4_gemm(a_, 7, b_, 8, M_, N_, K_, q4.B_KN, out=c_, workspace=w_), torch, reps=50, warm=5)
+        ex[f"gemm_{M_}x{N_}x{K_}_us"] = round(ms * 1e3, 2)
+
     # config 3: one conv layer + requant
     c = wl.config3()
     x = flat_pack(c.x_codes)
