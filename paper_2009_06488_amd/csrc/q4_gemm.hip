@@ -673,7 +673,7 @@ q4_gemm_direct_kernel(const KernelArgs p)
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                      :
                      : "s"(lds_byte), "v"(voffset), "s"(desc), "s"(soffset)
-                     : "memory", "m0");
+                     : "memory");  // m0 is reserved: the compiler neither allocates nor tracks it
     };
     // Load number j (0 .. GA + GB - 1) of depth step kt into ring slot `slot`.  The loads of a step
     // are spread over the fragment rows of the main loop: issued back to back by all eight waves
