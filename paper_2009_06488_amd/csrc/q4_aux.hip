@@ -157,15 +157,22 @@ repack_kn_to_nk_fast_kernel(const uint8_t *__restrict__ src, int K, int N, long 
         if (k0 + 2 * kp + 1 < K) y = *reinterpret_cast<const uint4 *>(src + (k0 + 2L * kp + 1) * ld_src + col_byte);
     }
     const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+    // Byte j of `even` / `odd` belongs to output row 8d + 2j (+1) and output byte kp.  Four lanes with
+    // consecutive kp transpose their 4 x 4 bytes among themselves (two exchanges), so that each
+    // lane ends up with four consecutive output bytes of ONE row and writes a dword, not four bytes.
+    const int j = kp & 3;
+    auto transpose4 = [&](uint32_t a) {
+        const uint32_t b = static_cast<uint32_t>(__shfl_xor(static_cast<int>(a), 1, 64));
+        const uint32_t t = (j & 1) ? (((b >> 8) & 0x00FF00FFu) | (a & 0xFF00FF00u)) : ((a & 0x00FF00FFu) | ((b & 0x00FF00FFu) << 8));
+        const uint32_t u = static_cast<uint32_t>(__shfl_xor(static_cast<int>(t), 2, 64));
+        return (j & 2) ? ((u >> 16) | (t & 0xFFFF0000u)) : ((t & 0x0000FFFFu) | (u << 16));
+    };
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
         const uint32_t even = (xs[d] & kLowNibbles) | ((ys[d] << 4) & 0xF0F0F0F0u);
         const uint32_t odd = ((xs[d] >> 4) & kLowNibbles) | (ys[d] & 0xF0F0F0F0u);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            out[32 * c + 8 * d + 2 * j][kp] = static_cast<uint8_t>(even >> (8 * j));
-            out[32 * c + 8 * d + 2 * j + 1][kp] = static_cast<uint8_t>(odd >> (8 * j));
-        }
+        *reinterpret_cast<uint32_t *>(&out[32 * c + 8 * d + 2 * j][kp & ~3]) = transpose4(even);
+        *reinterpret_cast<uint32_t *>(&out[32 * c + 8 * d + 2 * j + 1][kp & ~3]) = transpose4(odd);
     }
     __syncthreads();
     const int piece = threadIdx.x & 3;  // 16 bytes = 32 k values
