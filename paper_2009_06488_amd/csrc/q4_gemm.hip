@@ -29,8 +29,7 @@ constexpr int kChunks = kStepBytes / 16;     // 16-byte chunks per row per step
 constexpr uint32_t kLowNibbles = 0x0F0F0F0Fu;
 constexpr int kStages = 3;                   // depth steps resident in LDS
 
-enum LoadMode {
-    kDenseAligned = 0,  // rows 16-byte aligned, ceil(K/2) a multiple of 16
+enum LoadMode {       // of the general kernel; aligned dense operands go to the direct kernel instead
     kDenseGeneric = 1,  // any alignment, any K
     kConvAligned = 2,   // C a multiple of 32: every 16-byte chunk lies inside one tap
     kConvGeneric = 3,   // any C: gathered code by code
@@ -380,7 +379,7 @@ q4_gemm_kernel(const KernelArgs p)
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 fragments");
     static_assert(BM * kChunks % T == 0 && BN * kChunks % T == 0, "tile rows must divide over the threads");
     constexpr bool kConv = (MODE == kConvAligned || MODE == kConvGeneric || MODE == kConvHalf);
-    constexpr bool kAligned = (MODE == kDenseAligned || MODE == kConvAligned);
+    constexpr bool kAligned = (MODE == kConvAligned);  // weights read with range-checked 16-byte loads
 
     __shared__ uint4 lds[kStages][(BM + BN) * kChunks];
     __shared__ __attribute__((aligned(16))) int terms[BM + BN];
@@ -402,7 +401,6 @@ q4_gemm_kernel(const KernelArgs p)
     const int chunk = tid % kChunks;  // same for all of a thread's slots (T is a multiple of kChunks)
     const int chunk_limit = p.kbytes - chunk * 16;  // this thread's chunk of step kt exists iff kt * 64 < chunk_limit
     const uint8_t *a_row[NA];
-    uint32_t a_off[NA];
     PatchOrigin a_org[NA];
     int a_lds[NA];
 #pragma unroll
@@ -410,7 +408,6 @@ q4_gemm_kernel(const KernelArgs p)
         const int row = (tid + i * T) / kChunks;
         const long m = min(static_cast<long>(m0 + row), static_cast<long>(p.M - 1));
         if constexpr (kConv) a_org[i] = patch_origin(p.g, m);
-        else if constexpr (kAligned) a_off[i] = static_cast<uint32_t>(m * p.lda + chunk * 16);
         else a_row[i] = p.A + m * p.lda;
         a_lds[i] = row * kChunks + (chunk ^ swizzle(row));
     }
@@ -425,8 +422,7 @@ q4_gemm_kernel(const KernelArgs p)
         else b_row[i] = p.B + n * p.ldb;
         b_lds[i] = BM * kChunks + row * kChunks + (chunk ^ swizzle(row));
     }
-    __amdgpu_buffer_rsrc_t a_rsrc, b_rsrc;
-    if constexpr (MODE == kDenseAligned) a_rsrc = make_rsrc(p.A, p.a_bytes);
+    __amdgpu_buffer_rsrc_t b_rsrc;
     if constexpr (kAligned) b_rsrc = make_rsrc(p.B, p.b_bytes);
 
     v4u a_reg[NA], b_reg[NB];
@@ -439,9 +435,7 @@ q4_gemm_kernel(const KernelArgs p)
         const bool present = k0 < chunk_limit;
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            if constexpr (MODE == kDenseAligned) {
-                a_reg[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, present ? a_off[i] : kOutOfRange, k0, 0);
-            } else if constexpr (MODE == kConvAligned) {
+            if constexpr (MODE == kConvAligned) {
                 a_reg[i] = as_v4u(load_conv_chunk_aligned(p.A, p.g, a_org[i], kb, p.kbytes));
             } else if constexpr (MODE == kConvHalf) {
                 const uint2 h0 = load_conv_half_chunk(p.A, p.g, a_org[i], kb, p.kbytes);
