@@ -163,6 +163,20 @@ def test_gemm_extremes(za, zb, fa, fb):
     assert abs(got_const) <= 225 * K
 
 
+@pytest.mark.parametrize("M,N,K", [(70, 40, 65568), (1000, 999, 2080), (513, 1025, 4096)])
+def test_gemm_long_depth_and_ragged_large(M, N, K):
+    """Thousands of depth steps through the LDS ring; large ragged M and N with the tile chosen by shape."""
+    say("gemm large ragged", M, N, K)
+    rng = np.random.default_rng(K)
+    za, zb = (int(v) for v in rng.integers(0, 16, size=2))
+    A = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
+    Bnk = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    got = host(q4.q4_gemm(dev(A), za, dev(Bnk), zb, M, N, K, q4.B_NK))
+    assert np.array_equal(got, o.gemm_f64(A, za, Bnk, zb, M, N, K, o.B_NK))
+    rows = [0, M // 2, M - 1]
+    assert np.array_equal(got[rows], o.gemm_rows(A, za, Bnk, zb, rows, N, K, o.B_NK))
+
+
 def test_gemm_unaligned_views_and_ldc():
     say("gemm unaligned views")
     rng = np.random.default_rng(99)
