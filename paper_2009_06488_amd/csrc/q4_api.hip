@@ -135,7 +135,16 @@ int q4_gemm(int M, int N, int K,
             return Q4_ERR_HIP;
         B_nk = copy;
     }
-    if (q4::launch_rowsum2(A, M, lda_bytes, rowsumA, B_nk, N, ldb_nk, colsumB, K, s) != hipSuccess) return Q4_ERR_HIP;
+    // Small products are bound by launches, not by work: their depth sums are formed inside the product
+    // kernel while it loads the tiles (one launch less); large ones get the separate bandwidth-bound pass
+    // and the direct-to-LDS kernel.
+    const bool small = 2.0 * M * N * K <= 2.0e8 && tile_override() < 0;
+    if (small) {
+        rowsumA = nullptr;
+        colsumB = nullptr;
+    } else if (q4::launch_rowsum2(A, M, lda_bytes, rowsumA, B_nk, N, ldb_nk, colsumB, K, s) != hipSuccess) {
+        return Q4_ERR_HIP;
+    }
 
     q4::GemmProblem p{};
     p.M = M;

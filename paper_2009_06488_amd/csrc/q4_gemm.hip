@@ -33,6 +33,7 @@ enum LoadMode {       // of the general kernel; aligned dense operands go to the
     kDenseGeneric = 1,  // any alignment, any K
     kConvAligned = 2,   // C a multiple of 32: every 16-byte chunk lies inside one tap
     kConvGeneric = 3,   // any C: gathered code by code
+    kDenseSums = 5,     // as kDenseGeneric, and the depth sums of A and B are formed in the kernel (small problems)
     kConvHalf = 4       // C a multiple of 16: every 8-byte half chunk lies inside one tap; B by the general loader
 };
 
@@ -264,13 +265,14 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
 // ---- epilogue shared by both kernels.  The zero-point terms of Eq. (2) are staged in LDS
 // once per tile, before the main loop: row_term[r] = -zb * rowsumA[m0 + r] and
 // col_term[c] = K * za * zb - za * colsumB[n0 + c], so that C = raw + row_term + col_term.
-template <int BM, int BN, int T, bool ROWS = true>
+template <int BM, int BN, int T, bool ROWS = true, bool COLS = true>
 __device__ __forceinline__ void stage_terms(int *terms, const KernelArgs &p, int m0, int n0, int tid)
 {
     if constexpr (ROWS)
         for (int r = tid; r < BM; r += T) terms[r] = (m0 + r < p.M) ? -p.zb * (p.rowsumA[m0 + r] - p.sum_bias) : 0;
     const int kzz = p.K * p.za * p.zb - p.raw_bias;
-    for (int c = tid; c < BN; c += T) terms[BM + c] = (n0 + c < p.N) ? kzz - p.za * (p.colsumB[n0 + c] - p.sum_bias) : 0;
+    if constexpr (COLS)
+        for (int c = tid; c < BN; c += T) terms[BM + c] = (n0 + c < p.N) ? kzz - p.za * (p.colsumB[n0 + c] - p.sum_bias) : 0;
 }
 
 // In a 32x32 accumulator fragment register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4 and
@@ -379,6 +381,8 @@ q4_gemm_kernel(const KernelArgs p)
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 fragments");
     static_assert(BM * kChunks % T == 0 && BN * kChunks % T == 0, "tile rows must divide over the threads");
     constexpr bool kConv = (MODE == kConvAligned || MODE == kConvGeneric || MODE == kConvHalf);
+    constexpr bool kSumA = kConv || MODE == kDenseSums;  // row sums of A formed here, while the rows are loaded
+    constexpr bool kSumB = MODE == kDenseSums;           // likewise the sums of B's rows
     constexpr bool kAligned = (MODE == kConvAligned);  // weights read with range-checked 16-byte loads
 
     __shared__ uint4 lds[kStages][(BM + BN) * kChunks];
@@ -394,7 +398,7 @@ q4_gemm_kernel(const KernelArgs p)
     const int m0 = tm * BM, n0 = tn * BN;
     const bool odd_k = (p.K & 1) != 0;
     // published by the barriers of the main loop; convolutions sum their gathered rows themselves
-    stage_terms<BM, BN, T, !kConv>(terms, p, m0, n0, tid);
+    stage_terms<BM, BN, T, !kSumA, !kSumB>(terms, p, m0, n0, tid);
 
     // ---- what this thread copies from HBM to LDS at every step: NA chunks of A, NB of B.
     // Rows past M (or N) repeat the last valid row; their products are never stored.
@@ -426,9 +430,22 @@ q4_gemm_kernel(const KernelArgs p)
     if constexpr (kAligned) b_rsrc = make_rsrc(p.B, p.b_bytes);
 
     v4u a_reg[NA], b_reg[NB];
-    int a_sum[NA];  // convolution: running sum of the codes this thread has gathered for each of its rows
+    int a_sum[NA], b_sum[NB];  // running sums of the codes this thread has loaded for each of its rows
 #pragma unroll
     for (int i = 0; i < NA; ++i) a_sum[i] = 0;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) b_sum[i] = 0;
+    auto code_sum = [](const v4u &v) {
+        int sum = 0;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint32_t t = (v[d] & kLowNibbles) + ((v[d] >> 4) & kLowNibbles);  // four byte sums, each <= 30
+            t += t >> 16;
+            t += t >> 8;
+            sum += static_cast<int>(t & 0xFFu);
+        }
+        return sum;
+    };
     auto fetch = [&](int kt, v4u (&a_reg)[NA], v4u (&b_reg)[NB]) {
         const int k0 = kt * kStepBytes;
         const int kb = k0 + chunk * 16;
@@ -453,17 +470,9 @@ q4_gemm_kernel(const KernelArgs p)
                 a_reg[i] = as_v4u(load_dense_chunk_generic(a_row[i], kb, p.kbytes, odd_k));
             }
         }
-        if constexpr (kConv) {
+        if constexpr (kSumA) {
 #pragma unroll
-            for (int i = 0; i < NA; ++i)
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const uint32_t w = a_reg[i][d];
-                    uint32_t t = (w & kLowNibbles) + ((w >> 4) & kLowNibbles);  // four byte sums, each <= 30
-                    t += t >> 16;
-                    t += t >> 8;
-                    a_sum[i] += static_cast<int>(t & 0xFFu);
-                }
+            for (int i = 0; i < NA; ++i) a_sum[i] += code_sum(a_reg[i]);
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
@@ -471,6 +480,10 @@ q4_gemm_kernel(const KernelArgs p)
                 b_reg[i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, present ? b_off[i] : kOutOfRange, k0, 0);
             else
                 b_reg[i] = as_v4u(load_dense_chunk_generic(b_row[i], kb, p.kbytes, odd_k));
+        }
+        if constexpr (kSumB) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) b_sum[i] += code_sum(b_reg[i]);
         }
     };
     auto stash = [&](int buf, const v4u (&a_reg)[NA], const v4u (&b_reg)[NB]) {
@@ -566,16 +579,30 @@ q4_gemm_kernel(const KernelArgs p)
     }
 
     // ---- epilogue: add the zero-point terms of Eq. (2) and store
-    if constexpr (kConv) {
-        // Row sums of the virtual im2col matrix (Sec. 2.2 of the paper: computed while unrolling):
-        // the four threads that gathered the four chunks of a row are neighbours in the wave.
+    if constexpr (kSumA || kSumB) {
+        // Depth sums formed while loading (for convolutions: the row sums of the virtual im2col
+        // matrix, computed while unrolling as in Sec. 2.2 of the paper): the four threads that
+        // loaded the four chunks of a row are neighbours in the wave.
+        if constexpr (kSumA) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            int sum = a_sum[i];
-            sum += __shfl_xor(sum, 1, 64);
-            sum += __shfl_xor(sum, 2, 64);
-            const int row = (tid + i * T) / kChunks;
-            if (chunk == 0) terms[row] = (m0 + row < p.M) ? -p.zb * sum : 0;
+            for (int i = 0; i < NA; ++i) {
+                int sum = a_sum[i];
+                sum += __shfl_xor(sum, 1, 64);
+                sum += __shfl_xor(sum, 2, 64);
+                const int row = (tid + i * T) / kChunks;
+                if (chunk == 0) terms[row] = (m0 + row < p.M) ? -p.zb * sum : 0;
+            }
+        }
+        if constexpr (kSumB) {
+            const int kzz = p.K * p.za * p.zb;
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                int sum = b_sum[i];
+                sum += __shfl_xor(sum, 1, 64);
+                sum += __shfl_xor(sum, 2, 64);
+                const int row = (tid + i * T) / kChunks;
+                if (chunk == 0) terms[BM + row] = (n0 + row < p.N) ? kzz - p.za * sum : 0;
+            }
         }
         __syncthreads();
     }
@@ -867,7 +894,9 @@ hipError_t launch_tile(const GemmProblem &q, hipStream_t stream)
                            (q.K % 2 == 0) && b_extent < kMaxExtent;
     if (!q.is_conv) {
         const bool a_aligned = (reinterpret_cast<uintptr_t>(q.A) % 16 == 0) && (q.lda % 16 == 0) && a_extent < kMaxExtent;
-        if (a_aligned && b_aligned)
+        if (q.rowsumA == nullptr || q.colsumB == nullptr)
+            q4_gemm_kernel<BM, BN, WAVES_M, WAVES_N, kDenseSums><<<grid, block, 0, stream>>>(a);
+        else if (a_aligned && b_aligned)
             q4_gemm_direct_kernel<BM, BN, WAVES_M, WAVES_N, direct_stages(BM, BN, WAVES_M * WAVES_N)><<<grid, block, 0, stream>>>(a);
         else
             q4_gemm_kernel<BM, BN, WAVES_M, WAVES_N, kDenseGeneric><<<grid, block, 0, stream>>>(a);
