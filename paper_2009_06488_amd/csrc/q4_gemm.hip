@@ -205,7 +205,7 @@ __device__ __forceinline__ uint32_t load_conv_dword_generic(const uint8_t *x, co
     const int b = static_cast<int>(blockIdx.x) - p.stagger_first;
     if (p.stagger_ticks > 0 && b >= 0 && b < p.stagger_count) {
         const unsigned long long t0 = wall_clock64();
-        for (int spin = 0; spin < (1 << 16) && wall_clock64() - t0 < static_cast<unsigned long long>(p.stagger_ticks); ++spin)
+        for (int spin = 0; spin < (1 << 12) && wall_clock64() - t0 < static_cast<unsigned long long>(p.stagger_ticks); ++spin)
             __builtin_amdgcn_s_sleep(32);
     }
 }
@@ -879,7 +879,8 @@ hipError_t launch_tile(const GemmProblem &q, hipStream_t stream)
         const double tile_us = 2.0 * BM * BN * static_cast<double>(q.K) / 12.0e6;
         const char *e = getenv("Q4_STAGGER_PCT");
         const double pct = e ? atof(e) : 35.0;
-        a.stagger_ticks = static_cast<int>(tile_us * pct);  // 100 ticks per microsecond, pct / 100
+        const double ticks = tile_us * pct;  // 100 ticks per microsecond, pct / 100
+        a.stagger_ticks = static_cast<int>(ticks < 5000.0 ? ticks : 5000.0);  // never more than 50 us
     }
     const dim3 grid(static_cast<unsigned>(a.tiles_m) * static_cast<unsigned>(a.tiles_n));
     const dim3 block(WAVES_M * WAVES_N * 64);
