@@ -226,9 +226,10 @@ __device__ __forceinline__ v4i low_codes(const v4u &p) { return (v4i)(p & kLowNi
 // those bits are dead, splits a 64-bit shift back into two 32-bit ones.
 __device__ __forceinline__ uint64_t shift_pair(uint32_t lo, uint32_t hi)
 {
-    uint64_t v = (static_cast<uint64_t>(hi) << 32) | lo;
-    asm("v_lshrrev_b64 %0, 4, %0" : "+v"(v));
-    return v;
+    const uint64_t v = (static_cast<uint64_t>(hi) << 32) | lo;
+    uint64_t shifted;  // a separate destination: the packed source is still needed for the low nibbles
+    asm("v_lshrrev_b64 %0, 4, %1" : "=v"(shifted) : "v"(v));
+    return shifted;
 }
 
 __device__ __forceinline__ v4i high_codes(const v4u &p)
