@@ -1,0 +1,19 @@
+"""Host-only checks of bench.py's command-line contract."""
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_default_arguments():
+    src = open(os.path.join(ROOT, "bench.py")).read()
+    assert '"--gpus", type=int, default=1' in src
+    assert '"--steps", type=int' in src and '"--warmup", type=int' in src
