@@ -284,6 +284,11 @@ def _extras(q4, wl, torch, np, dev):
         for L, wt, ws_ in zip(case.layers, weights, wsums):
             dd = q4.conv_desc(case.batch, H, W, cin, 3, 3, (1, 1), (case.pad, case.pad), L.cout)
             H, W = q4.conv_out_hw(dd)
+            if fused and L.pool_after:
+                act = q4.q4_conv2d_requant_pool2x2(dd, act, zx, wt, L.zw, L.mult, L.shift, L.zo, w_colsum=ws_)
+                zx, cin = L.zo, L.cout
+                H, W = H // 2, W // 2
+                continue
             if fused:
                 act = q4.q4_conv2d_requant(dd, act, zx, wt, L.zw, L.mult, L.shift, L.zo, w_colsum=ws_).reshape(-1)
             else:

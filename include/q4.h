@@ -178,6 +178,21 @@ int q4_conv2d_requant(const q4_conv_desc *desc, const uint8_t *x, int zx,
                       uint8_t *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * q4_conv2d_requant_pool2x2 -- q4_conv2d_requant followed by q4_maxpool2x2 in one call; when
+ * the output tiles of the product kernel hold whole pairs of image rows (OH and OW even, 2*OW
+ * dividing the tile height) the pooling happens in the kernel's epilogue and neither the int32
+ * result nor the unpooled codes go to memory; otherwise the two kernels run back to back.
+ * Result identical to the separate calls.  OC must be even.
+ *   out : N x (OH/2) x (OW/2) x OC packed codes.
+ *   workspace : >= q4_conv2d_pool_workspace_bytes(desc), 16-byte aligned.
+ */
+size_t q4_conv2d_pool_workspace_bytes(const q4_conv_desc *desc);
+int q4_conv2d_requant_pool2x2(const q4_conv_desc *desc, const uint8_t *x, int zx,
+                              const uint8_t *w, int zw, const int32_t *w_colsum,
+                              int32_t mult, int shift, int zo, int qmin, int qmax,
+                              uint8_t *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * q4_requant -- bring an int32 layer output back to 4-bit codes for the next
  * quantized layer (the Q -> Q transition of Sec. 3.2), in integer form:
  *   out(r, c) = min(max(floor(acc[r*ld_acc + c] * mult / 2^shift) + zo, qmin), qmax)

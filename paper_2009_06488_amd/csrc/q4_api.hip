@@ -289,6 +289,56 @@ int q4_conv2d_requant(const q4_conv_desc *d, const uint8_t *x, int zx,
     return conv_forward(d, x, zx, w, zw, w_colsum, nullptr, rq, workspace, workspace_bytes, stream);
 }
 
+size_t q4_conv2d_pool_workspace_bytes(const q4_conv_desc *d)
+{
+    int OH, OW;
+    if (!d || !conv_out_dims(d, &OH, &OW)) return 0;
+    // the weight sums, and room for the unpooled codes when pooling cannot be fused into the epilogue
+    return q4_conv2d_workspace_bytes(d) + align_up(static_cast<size_t>(d->N) * OH * OW * ((d->OC + 1) / 2), 16);
+}
+
+int q4_conv2d_requant_pool2x2(const q4_conv_desc *d, const uint8_t *x, int zx,
+                              const uint8_t *w, int zw, const int32_t *w_colsum,
+                              int32_t mult, int shift, int zo, int qmin, int qmax,
+                              uint8_t *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!d || !x || !w || !out) return Q4_ERR_NULL;
+    int OH, OW;
+    if (!conv_out_dims(d, &OH, &OW) || OH < 2 || OW < 2 || (d->OC & 1)) return Q4_ERR_SHAPE;
+    if (mult < 0 || shift < 0 || shift > 62) return Q4_ERR_RANGE;
+    if (!code_ok(zo) || !code_ok(qmin) || !code_ok(qmax) || qmin > qmax) return Q4_ERR_RANGE;
+    if (!workspace || workspace_bytes < q4_conv2d_pool_workspace_bytes(d)) return Q4_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16) return Q4_ERR_ALIGN;
+    q4::Requant rq{};
+    rq.ld_out = (d->OC + 1) / 2;
+    rq.mult = mult;
+    rq.shift = shift;
+    rq.zo = zo;
+    rq.qmin = qmin;
+    rq.qmax = qmax;
+    // Can the product kernel pool in its epilogue?  (whole pairs of image rows per tile)
+    q4::GemmProblem probe{};
+    probe.is_conv = true;
+    probe.M = d->N * OH * OW;
+    probe.N = d->OC;
+    probe.g.OH = OH;
+    probe.g.KH = d->KH;
+    probe.g.KW = d->KW;
+    probe.g.C = d->C;
+    probe.rq.pool_ow = OW;
+    const bool small_depth = q4::conv_small_depth_applies(probe.g, d->OC);
+    if (tile_override() < 0 && !small_depth && q4::gemm_can_pool(probe)) {
+        rq.out = out;
+        rq.pool_ow = OW;
+        return conv_forward(d, x, zx, w, zw, w_colsum, nullptr, rq, workspace, q4_conv2d_workspace_bytes(d), stream);
+    }
+    uint8_t *codes = static_cast<uint8_t *>(workspace) + q4_conv2d_workspace_bytes(d);
+    rq.out = codes;
+    const int rc = conv_forward(d, x, zx, w, zw, w_colsum, nullptr, rq, workspace, q4_conv2d_workspace_bytes(d), stream);
+    if (rc != Q4_OK) return rc;
+    return rc_of(q4::launch_maxpool2x2(codes, d->N, OH, OW, d->OC, out, static_cast<hipStream_t>(stream)));
+}
+
 int q4_requant(const int32_t *acc, long rows, int cols, long ld_acc,
                int32_t mult, int shift, int zo, int qmin, int qmax,
                uint8_t *out, long ld_out_bytes, void *stream)

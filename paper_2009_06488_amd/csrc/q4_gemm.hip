@@ -344,8 +344,32 @@ __device__ __forceinline__ void store_tile_requant(const v16i (&acc)[FM][FN], co
         }
     }
     __syncthreads();
-    // one thread per output byte (two codes); consecutive threads write consecutive bytes of a row
     constexpr int kRowBytes = BN / 2;
+    if (p.rq.pool_ow > 0) {
+        // Fused 2x2 max-pool (valid on codes: the re-quantization is monotone).  The tile holds whole
+        // pairs of image rows (BM is a multiple of 2 * OW, the launcher checked), so every window is
+        // inside it, and pooled pixel number m0 / 4 + pl is simply the pl-th window of the tile.
+        const int ow = p.rq.pool_ow, half_ow = ow >> 1;
+        for (int idx = tid; idx < (BM / 4) * kRowBytes; idx += T) {
+            const int pl = idx / kRowBytes, b = idx % kRowBytes;
+            const int r00 = (pl / half_ow) * 2 * ow + (pl % half_ow) * 2;
+            const long pixel = (m0 >> 2) + pl;
+            const int n = n0 + 2 * b;
+            if (pixel < (p.M >> 2) && n < p.N) {
+                uint32_t v = 0;
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const uint8_t *s0 = stage + r00 * kPitch + 2 * b + c;
+                    const uint32_t top = max(static_cast<uint32_t>(s0[0]), static_cast<uint32_t>(s0[kPitch]));
+                    const uint32_t bottom = max(static_cast<uint32_t>(s0[ow * kPitch]), static_cast<uint32_t>(s0[(ow + 1) * kPitch]));
+                    if (n + c < p.N) v |= max(top, bottom) << (4 * c);
+                }
+                p.rq.out[pixel * p.rq.ld_out + (n >> 1)] = static_cast<uint8_t>(v);
+            }
+        }
+        return;
+    }
+    // one thread per output byte (two codes); consecutive threads write consecutive bytes of a row
     for (int idx = tid; idx < BM * kRowBytes; idx += T) {
         const int r = idx / kRowBytes, b = idx % kRowBytes;
         const int m = m0 + r, n = n0 + 2 * b;
@@ -953,20 +977,47 @@ hipError_t launch_tile8(const GemmProblem &q, hipStream_t stream)
 
 hipError_t launch_gemm8(const GemmProblem &p, hipStream_t stream) { return launch_tile8(p, stream); }
 
+namespace {
+// The tile is as wide as the output needs (few output channels are the rule for convolutions) and as
+// tall as still leaves enough tiles for 256 compute units.
+int tile_by_shape(const GemmProblem &p)
+{
+    auto tiles = [&](long bm, long bn) { return ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
+    if (p.N <= 32) return 7;
+    if (p.N <= 64) return tiles(256, 64) >= 256 ? 6 : 2;
+    if (p.N <= 128) return tiles(256, 128) >= 256 ? 3 : (tiles(128, 128) >= 128 ? 1 : 2);
+    if (tiles(256, 256) >= 256) return 0;
+    if (tiles(128, 128) >= 128) return 1;
+    return 2;
+}
+constexpr int kTileRows[8] = {256, 128, 64, 256, 128, 256, 256, 128};
+}  // namespace
+
+// Tile for a convolution whose epilogue also pools: every 2x2 window must lie inside one tile, i.e. the
+// tile height must be a multiple of two image rows.  The shape-chosen tile if it qualifies, else another
+// one of the same width class; -1 if none does.
+static int tile_for_pool(const GemmProblem &p)
+{
+    const int ow = p.rq.pool_ow;
+    if (!p.is_conv || ow <= 0 || ow % 2 || p.g.OH % 2) return -1;
+    const int preferred = tile_by_shape(p);
+    if (kTileRows[preferred] % (2 * ow) == 0) return preferred;
+    const int by_width[4][3] = {{7, -1, -1}, {6, 2, -1}, {3, 1, 2}, {0, 1, 2}};
+    const int cls = p.N <= 32 ? 0 : p.N <= 64 ? 1 : p.N <= 128 ? 2 : 3;
+    for (int i = 0; i < 3; ++i) {
+        const int t = by_width[cls][i];
+        if (t >= 0 && kTileRows[t] % (2 * ow) == 0) return t;
+    }
+    return -1;
+}
+
+bool gemm_can_pool(const GemmProblem &p) { return tile_for_pool(p) >= 0; }
+
 hipError_t launch_gemm(const GemmProblem &p, int force_tile, hipStream_t stream)
 {
     int tile = force_tile;
-    if (tile < 0) {
-        // The tile is as wide as the output needs (few output channels are the rule for
-        // convolutions) and as tall as still leaves enough tiles for 256 compute units.
-        auto tiles = [&](long bm, long bn) { return ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
-        if (p.N <= 32) tile = 7;
-        else if (p.N <= 64) tile = tiles(256, 64) >= 256 ? 6 : 2;
-        else if (p.N <= 128) tile = tiles(256, 128) >= 256 ? 3 : (tiles(128, 128) >= 128 ? 1 : 2);
-        else if (tiles(256, 256) >= 256) tile = 0;
-        else if (tiles(128, 128) >= 128) tile = 1;
-        else tile = 2;
-    }
+    if (tile < 0) tile = p.rq.pool_ow > 0 ? tile_for_pool(p) : tile_by_shape(p);
+    if (tile < 0) return hipErrorInvalidValue;  // pooling asked for without checking gemm_can_pool
     switch (tile) {
     case 0: return launch_tile<256, 256, 2, 4>(p, stream);
     case 1: return launch_tile<128, 128, 2, 2>(p, stream);

@@ -22,6 +22,7 @@ struct Requant {
     uint8_t *out;   // M rows of ceil(N/2) bytes, or nullptr
     long ld_out;    // bytes between rows
     int mult, shift, zo, qmin, qmax;
+    int pool_ow;    // > 0: also 2x2 max-pool; the rows are output pixels of images OW = pool_ow wide (tiled kernel only)
 };
 
 struct GemmProblem {
@@ -43,6 +44,8 @@ struct GemmProblem {
 // Main product + zero-point epilogue: C = raw - za*colsumB[n] - zb*rowsumA[m] + K*za*zb.
 // `force_tile` < 0 picks the tile by shape; 0..2 force large / medium / small.
 hipError_t launch_gemm(const GemmProblem &p, int force_tile, hipStream_t stream);
+// Whether launch_gemm (shape-chosen tile) can pool in its epilogue for this problem (p.rq.pool_ow set).
+bool gemm_can_pool(const GemmProblem &p);
 
 hipError_t launch_pack(const uint8_t *src, int rows, int cols, int ld_src, int transpose,
                        uint8_t *dst, int ld_dst, hipStream_t stream);

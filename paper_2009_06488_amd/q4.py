@@ -24,6 +24,7 @@ B_KN, B_NK = 0, 1
 EXPORTS = (
     "q4_version", "q4_strerror", "q4_max_depth", "q4_pack", "q4_rowsum", "q4_repack_kn_to_nk",
     "q4_gemm_workspace_bytes", "q4_gemm", "q4_gemm_presummed", "q4_conv2d_workspace_bytes", "q4_conv2d_im2col", "q4_conv2d_requant",
+    "q4_conv2d_pool_workspace_bytes", "q4_conv2d_requant_pool2x2",
     "q4_requant", "q4_maxpool2x2", "q4_debug_force_tile",
     "q4_quantize_workspace_bytes", "q4_quantize_f32", "q4_dequant_f32", "q8_gemm_workspace_bytes", "q8_gemm",
 )
@@ -62,6 +63,9 @@ def _load() -> ctypes.CDLL:
     lib.q4_conv2d_workspace_bytes.restype = Z
     lib.q4_conv2d_im2col.argtypes = [ctypes.POINTER(ConvDesc), P, I, P, I, P, P, P, Z, P]
     lib.q4_conv2d_requant.argtypes = [ctypes.POINTER(ConvDesc), P, I, P, I, P, ctypes.c_int32, I, I, I, I, P, P, Z, P]
+    lib.q4_conv2d_pool_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
+    lib.q4_conv2d_pool_workspace_bytes.restype = Z
+    lib.q4_conv2d_requant_pool2x2.argtypes = [ctypes.POINTER(ConvDesc), P, I, P, I, P, ctypes.c_int32, I, I, I, I, P, P, Z, P]
     lib.q4_requant.argtypes = [P, L, I, L, ctypes.c_int32, I, I, I, I, P, L, P]
     lib.q4_maxpool2x2.argtypes = [P, I, I, I, I, P, P]
     lib.q4_quantize_workspace_bytes.restype = Z
@@ -250,6 +254,28 @@ def q4_conv2d_requant(desc: ConvDesc, x: torch.Tensor, zx: int, w: torch.Tensor,
     _check(lib.q4_conv2d_requant(ctypes.byref(desc), _dev(x, torch.uint8), zx, _dev(w, torch.uint8), zw, cs,
                                  mult, shift, zo, qmin, qmax, _dev(out, torch.uint8),
                                  _dev(workspace, torch.uint8), workspace.numel(), _stream()), "q4_conv2d_requant")
+    return out
+
+
+def q4_conv2d_requant_pool2x2(desc: ConvDesc, x: torch.Tensor, zx: int, w: torch.Tensor, zw: int,
+                              mult: int, shift: int, zo: int, qmin: int = 0, qmax: int = 15,
+                              w_colsum: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                              workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Convolution + re-quantization + 2x2 max-pool -> flat packed N x OH/2 x OW/2 x OC codes."""
+    assert w.is_contiguous() and x.is_contiguous()
+    OH, OW = conv_out_hw(desc)
+    n_out = desc.N * (OH // 2) * (OW // 2) * desc.OC
+    if out is None:
+        out = torch.empty((n_out + 1) // 2, dtype=torch.uint8, device=x.device)
+    assert out.is_contiguous() and 2 * out.numel() >= n_out
+    _conv_shapes(desc, x, w, w_colsum)
+    if workspace is None:
+        workspace = _workspace(int(lib.q4_conv2d_pool_workspace_bytes(ctypes.byref(desc))), x.device)
+    cs = _dev(w_colsum, torch.int32) if w_colsum is not None else None
+    _check(lib.q4_conv2d_requant_pool2x2(ctypes.byref(desc), _dev(x, torch.uint8), zx, _dev(w, torch.uint8), zw, cs,
+                                         mult, shift, zo, qmin, qmax, _dev(out, torch.uint8),
+                                         _dev(workspace, torch.uint8), workspace.numel(), _stream()),
+           "q4_conv2d_requant_pool2x2")
     return out
 
 

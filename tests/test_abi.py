@@ -101,6 +101,17 @@ def test_other_argument_errors():
     assert L.q4_conv2d_im2col(ctypes.byref(bad), FAKE, 0, FAKE, 0, None, FAKE, FAKE, 1 << 20, None) == q4.ERR_SHAPE
 
 
+def test_pool_entry_argument_errors():
+    L = q4.lib
+    d = q4.conv_desc(1, 8, 8, 4, 3, 3, (1, 1), (1, 1), 4)
+    ref = ctypes.byref(d)
+    assert L.q4_conv2d_pool_workspace_bytes(ref) == 16 + 8 * 8 * 2
+    assert L.q4_conv2d_requant_pool2x2(ref, FAKE, 0, FAKE, 0, None, 1, 20, 8, 0, 15, None, FAKE, 1 << 20, None) == q4.ERR_NULL
+    assert L.q4_conv2d_requant_pool2x2(ref, FAKE, 0, FAKE, 0, None, 1, 20, 8, 0, 15, FAKE, FAKE, 32, None) == q4.ERR_WORKSPACE
+    odd = q4.conv_desc(1, 8, 8, 4, 3, 3, (1, 1), (1, 1), 5)
+    assert L.q4_conv2d_requant_pool2x2(ctypes.byref(odd), FAKE, 0, FAKE, 0, None, 1, 20, 8, 0, 15, FAKE, FAKE, 1 << 20, None) == q4.ERR_SHAPE
+
+
 def test_float_boundary_argument_errors():
     L = q4.lib
     assert q4.lib.q4_quantize_workspace_bytes() == 8192

@@ -357,6 +357,11 @@ def cnn_forward_gpu(case, x_codes, fused=False):
         w = dev(o.pack(L.w_codes.reshape(L.cout, -1)))
         d = q4.conv_desc(N, H, W, cin, 3, 3, (1, 1), (case.pad, case.pad), L.cout)
         H, W = q4.conv_out_hw(d)
+        if fused and L.pool_after:
+            act = q4.q4_conv2d_requant_pool2x2(d, act, zx, w, L.zw, L.mult, L.shift, L.zo)
+            zx, cin = L.zo, L.cout
+            H, W = H // 2, W // 2
+            continue
         if fused:
             act = q4.q4_conv2d_requant(d, act, zx, w, L.zw, L.mult, L.shift, L.zo).reshape(-1)
         else:
@@ -432,6 +437,30 @@ def test_gemm8_sibling(M, N, K):
         za, zb = 0, 255
     got = host(q4.q8_gemm(dev(a), za, dev(b), zb, M, N, K))
     assert np.array_equal(got, o.gemm8(a, za, b, zb))
+
+
+POOL_CASES = [
+    # N, H, W, C, OC  (3x3, stride 1, pad 1): fused in the epilogue when the tile holds whole row pairs
+    (2, 32, 128, 16, 32),   # config 4 layer 2: OW = 128, 128-row tiles -> falls back to two kernels
+    (2, 16, 64, 32, 64),    # config 4 layer 4: OW = 64 -> fused
+    (3, 8, 16, 32, 128),    # fused, small tiles
+    (1, 6, 10, 32, 6),      # OW = 10 does not divide any tile height -> fallback
+    (2, 4, 4, 1, 16),       # small-depth path -> fallback
+]
+
+
+@pytest.mark.parametrize("N,H,W,C,OC", POOL_CASES)
+def test_conv_requant_pool(N, H, W, C, OC):
+    say("conv+requant+pool", N, H, W, C, OC)
+    c = wl.conv_case("t", N, H, W, C, 3, 3, (1, 1), (1, 1), OC, zx=7, zw=8, shift=20, zo=8, seed=N * 100 + W + OC)
+    x = flat_pack(c.x_codes)
+    w = o.pack(c.w_codes.reshape(OC, -1))
+    y = o.conv2d(x, c.zx, w, c.zw, N, H, W, C, 3, 3, c.stride, c.pad, OC)
+    codes = o.requant(y, c.mult, c.shift, c.zo)
+    want = o.maxpool2x2(codes.reshape(-1), N, H, W, OC)
+    d = q4.conv_desc(N, H, W, C, 3, 3, c.stride, c.pad, OC)
+    got = host(q4.q4_conv2d_requant_pool2x2(d, dev(x), c.zx, dev(w), c.zw, c.mult, c.shift, c.zo))
+    assert np.array_equal(got, want)
 
 
 def test_paper_cnn_topology():
