@@ -34,38 +34,39 @@ __device__ __forceinline__ uint32_t load_dword_guarded(const uint8_t *row, long 
 }
 
 // ---------------------------------------------------------------- pack (no transpose)
-// One thread writes one output byte group of 4 (8 codes).
+// One thread packs 16 codes (a 16-byte load) into 8 bytes when the row allows, else code by code.
 __global__ void __launch_bounds__(256)
 pack_rows_kernel(const uint8_t *__restrict__ src, int rows, int cols, long ld_src,
                  uint8_t *__restrict__ dst, long ld_dst)
 {
     const int out_bytes = (cols + 1) >> 1;
-    const int groups = (out_bytes + 3) >> 2;
+    const int groups = (out_bytes + 7) >> 3;
     const long total = static_cast<long>(rows) * groups;
+    auto pack4 = [](uint32_t v) {  // four codes in four bytes -> four nibbles in the low 16 bits
+        v &= kLowNibbles;
+        v |= v >> 4;                      // byte0 = c0|c1<<4, byte2 = c2|c3<<4
+        return (v & 0xFFu) | ((v >> 8) & 0xFF00u);
+    };
     for (long idx = blockIdx.x * 256L + threadIdx.x; idx < total; idx += 256L * gridDim.x) {
         const int r = static_cast<int>(idx / groups);
         const int g = static_cast<int>(idx - static_cast<long>(r) * groups);
-        const uint8_t *s = src + r * ld_src + 8L * g;
-        uint8_t *d = dst + r * ld_dst + 4L * g;
-        const int c0 = 8 * g;
-        uint32_t w = 0;
-        if (c0 + 8 <= cols && (reinterpret_cast<uintptr_t>(s) & 7u) == 0) {
-            const uint2 v = *reinterpret_cast<const uint2 *>(s);
-            const uint32_t lo = v.x & kLowNibbles, hi = v.y & kLowNibbles;
-            // bytes (c0..c3) -> nibbles
-            uint32_t a = (lo | (lo >> 4));           // byte0 = c0|c1<<4, byte2 = c2|c3<<4
-            uint32_t b = (hi | (hi >> 4));
-            w = (a & 0xFFu) | ((a >> 8) & 0xFF00u) | ((b & 0xFFu) << 16) | ((b << 8) & 0xFF000000u);
+        const uint8_t *s = src + r * ld_src + 16L * g;
+        uint8_t *d = dst + r * ld_dst + 8L * g;
+        const int c0 = 16 * g;
+        if (c0 + 16 <= cols && (reinterpret_cast<uintptr_t>(s) & 15u) == 0 && (reinterpret_cast<uintptr_t>(d) & 7u) == 0) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(s);
+            uint2 w;
+            w.x = pack4(v.x) | (pack4(v.y) << 16);
+            w.y = pack4(v.z) | (pack4(v.w) << 16);
+            *reinterpret_cast<uint2 *>(d) = w;
         } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (c0 + j < cols) w |= static_cast<uint32_t>(s[j] & 15u) << (4 * j);
-        }
-        if (4 * g + 4 <= out_bytes && (reinterpret_cast<uintptr_t>(d) & 3u) == 0) {
-            *reinterpret_cast<uint32_t *>(d) = w;
-        } else {
-            for (int j = 0; j < 4; ++j)
-                if (4 * g + j < out_bytes) d[j] = static_cast<uint8_t>(w >> (8 * j));
+            for (int b = 0; b < 8; ++b) {
+                const int c = c0 + 2 * b;
+                if (8 * g + b >= out_bytes) break;
+                uint32_t v = s[2 * b] & 15u;
+                if (c + 1 < cols) v |= static_cast<uint32_t>(s[2 * b + 1] & 15u) << 4;
+                d[b] = static_cast<uint8_t>(v);
+            }
         }
     }
 }
@@ -212,7 +213,16 @@ rowsum_kernel(const uint8_t *__restrict__ A, int rows, int k, long ld, int32_t *
         const bool fast = ((reinterpret_cast<uintptr_t>(row) & 15u) == 0) && (rowbytes % 16 == 0) && !(k & 1);
         if (fast) {
             const uint4 *row4 = reinterpret_cast<const uint4 *>(row);
-            for (int i = sub; i < rowbytes / 16; i += LANES) {
+            const int n16 = rowbytes / 16;
+            int i = sub;
+            for (; i + 3 * LANES < n16; i += 4 * LANES) {  // four loads in flight per lane
+                const uint4 v0 = row4[i], v1 = row4[i + LANES], v2 = row4[i + 2 * LANES], v3 = row4[i + 3 * LANES];
+                s += nibble_sum8(v0.x) + nibble_sum8(v0.y) + nibble_sum8(v0.z) + nibble_sum8(v0.w);
+                s += nibble_sum8(v1.x) + nibble_sum8(v1.y) + nibble_sum8(v1.z) + nibble_sum8(v1.w);
+                s += nibble_sum8(v2.x) + nibble_sum8(v2.y) + nibble_sum8(v2.z) + nibble_sum8(v2.w);
+                s += nibble_sum8(v3.x) + nibble_sum8(v3.y) + nibble_sum8(v3.z) + nibble_sum8(v3.w);
+            }
+            for (; i < n16; i += LANES) {
                 const uint4 v = row4[i];
                 s += nibble_sum8(v.x) + nibble_sum8(v.y) + nibble_sum8(v.z) + nibble_sum8(v.w);
             }
@@ -570,7 +580,7 @@ hipError_t launch_pack(const uint8_t *src, int rows, int cols, int ld_src, int t
                        uint8_t *dst, int ld_dst, hipStream_t stream)
 {
     if (!transpose) {
-        const long groups = static_cast<long>(rows) * ((((cols + 1) >> 1) + 3) >> 2);
+        const long groups = static_cast<long>(rows) * ((((cols + 1) >> 1) + 7) >> 3);
         pack_rows_kernel<<<grid_for(groups, 256, 1 << 16), 256, 0, stream>>>(src, rows, cols, ld_src, dst, ld_dst);
     } else {
         dim3 grid((cols + kT - 1) / kT, (rows + kT - 1) / kT);
@@ -672,11 +682,39 @@ hipError_t launch_dequant_f32(const int32_t *acc, long n, float scale, float *ou
     return hipGetLastError();
 }
 
+// 16 bytes (32 channels) per thread: four dwords through the same per-nibble maximum.
+__global__ void __launch_bounds__(256)
+maxpool2x2_vec_kernel(const uint8_t *__restrict__ x, int N, int H, int W, int Cv, uint8_t *__restrict__ y)
+{
+    const int OH = H >> 1, OW = W >> 1;
+    const long total = static_cast<long>(N) * OH * OW * Cv;
+    const uint4 *xi = reinterpret_cast<const uint4 *>(x);
+    uint4 *yo = reinterpret_cast<uint4 *>(y);
+    for (long idx = blockIdx.x * 256L + threadIdx.x; idx < total; idx += 256L * gridDim.x) {
+        const int c = static_cast<int>(idx % Cv);
+        long t = idx / Cv;
+        const int j = static_cast<int>(t % OW);
+        t /= OW;
+        const int i = static_cast<int>(t % OH);
+        const long n = t / OH;
+        const long p00 = ((n * H + 2 * i) * W + 2 * j) * Cv + c;
+        const uint4 a = xi[p00], b = xi[p00 + Cv], d = xi[p00 + static_cast<long>(W) * Cv], e = xi[p00 + static_cast<long>(W) * Cv + Cv];
+        uint4 r;
+        r.x = nibble_max<uint32_t>(nibble_max<uint32_t>(a.x, b.x), nibble_max<uint32_t>(d.x, e.x));
+        r.y = nibble_max<uint32_t>(nibble_max<uint32_t>(a.y, b.y), nibble_max<uint32_t>(d.y, e.y));
+        r.z = nibble_max<uint32_t>(nibble_max<uint32_t>(a.z, b.z), nibble_max<uint32_t>(d.z, e.z));
+        r.w = nibble_max<uint32_t>(nibble_max<uint32_t>(a.w, b.w), nibble_max<uint32_t>(d.w, e.w));
+        yo[idx] = r;
+    }
+}
+
 hipError_t launch_maxpool2x2(const uint8_t *x, int N, int H, int W, int C, uint8_t *y, hipStream_t stream)
 {
     const long out_px = static_cast<long>(N) * (H / 2) * (W / 2);
     const bool aligned = (reinterpret_cast<uintptr_t>(x) % 4 == 0) && (reinterpret_cast<uintptr_t>(y) % 4 == 0);
-    if (C % 8 == 0 && aligned) {
+    if (C % 32 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0) {
+        maxpool2x2_vec_kernel<<<grid_for(out_px * (C / 32), 256, 1 << 16), 256, 0, stream>>>(x, N, H, W, C / 32, y);
+    } else if (C % 8 == 0 && aligned) {
         maxpool2x2_kernel<uint32_t><<<grid_for(out_px * (C / 8), 256, 1 << 16), 256, 0, stream>>>(x, N, H, W, C / 8, y);
     } else {
         maxpool2x2_kernel<uint8_t><<<grid_for(out_px * (C / 2), 256, 1 << 16), 256, 0, stream>>>(x, N, H, W, C / 2, y);
