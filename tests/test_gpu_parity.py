@@ -177,6 +177,25 @@ def test_gemm_long_depth_and_ragged_large(M, N, K):
     assert np.array_equal(got[rows], o.gemm_rows(A, za, Bnk, zb, rows, N, K, o.B_NK))
 
 
+def test_gemm_at_the_depth_bound():
+    """K = floor((2^31 - 1) / 225): the all-fifteen product is the largest value int32 must hold."""
+    K = q4.max_depth()
+    say("gemm at the depth bound", K)
+    rng = np.random.default_rng(4)
+    a = np.full((2, K), 15, np.uint8)
+    b = np.full((3, K), 15, np.uint8)
+    a[1] = rng.integers(0, 16, size=K, dtype=np.uint8)
+    b[2] = rng.integers(0, 16, size=K, dtype=np.uint8)
+    A, Bnk = o.pack(a), o.pack(b)
+    for za, zb in ((0, 0), (15, 15), (7, 8)):
+        got = host(q4.q4_gemm(dev(A), za, dev(Bnk), zb, 2, 3, K, q4.B_NK))
+        assert np.array_equal(got, o.gemm(A, za, Bnk, zb, 2, 3, K, o.B_NK))
+    assert int(got.max()) <= 2 ** 31 - 1
+    with pytest.raises(q4.Q4Error) as e:
+        q4.q4_gemm(dev(A), 0, dev(Bnk), 0, 2, 3, K + 1, q4.B_NK)
+    assert e.value.code == q4.ERR_OVERFLOW
+
+
 def test_gemm_unaligned_views_and_ldc():
     say("gemm unaligned views")
     rng = np.random.default_rng(99)
