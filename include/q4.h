@@ -255,9 +255,8 @@ int q4_maxpool2x2(const uint8_t *x, int N, int H, int W, int C, uint8_t *y, void
 /*
  * q4_debug_force_tile -- testing hook: force the output-tile size q4_gemm and
  * q4_conv2d_im2col use (0 = 256x256, 1 = 128x128, 2 = 64x64, 3 = 256x128,
- * 4 = 128x256, 5 = 256x256 with four waves, 6 = 256x64, 7 = 128x32; anything
- * else restores selection by shape).  The result never depends on the tile.  The
- * environment variable Q4_TILE=0..7 does the same when no override is set.
+ * 6 = 256x64, 7 = 128x32; any other value restores selection by shape).  The result never depends on the tile.  The
+ * environment variable Q4_TILE (one of those digits) does the same when no override is set.
  * Host only; not thread-safe.
  */
 void q4_debug_force_tile(int tile);

@@ -20,7 +20,8 @@ int tile_override()
 {
     if (g_force_tile >= 0) return g_force_tile;
     const char *e = getenv("Q4_TILE");
-    if (e && e[0] >= '0' && e[0] <= '9' && e[1] == 0) return e[0] - '0';
+    if (e && e[1] == 0 && (e[0] == '0' || e[0] == '1' || e[0] == '2' || e[0] == '3' || e[0] == '6' || e[0] == '7'))
+        return e[0] - '0';
     return -1;
 }
 
@@ -66,7 +67,11 @@ const char *q4_strerror(int code)
 
 int q4_max_depth(void) { return kMaxDepth; }
 
-void q4_debug_force_tile(int tile) { g_force_tile = (tile >= 0 && tile <= 9) ? tile : -1; }
+void q4_debug_force_tile(int tile)
+{
+    const bool known = tile == 0 || tile == 1 || tile == 2 || tile == 3 || tile == 6 || tile == 7;
+    g_force_tile = known ? tile : -1;
+}
 
 int q4_pack(const uint8_t *src, int rows, int cols, int ld_src, int transpose,
             uint8_t *dst, int ld_dst_bytes, void *stream)

@@ -1022,8 +1022,6 @@ hipError_t launch_gemm(const GemmProblem &p, int force_tile, hipStream_t stream)
     case 0: return launch_tile<256, 256, 2, 4>(p, stream);
     case 1: return launch_tile<128, 128, 2, 2>(p, stream);
     case 3: return launch_tile<256, 128, 2, 2>(p, stream);
-    case 4: return launch_tile<128, 256, 2, 2>(p, stream);
-    case 5: return launch_tile<256, 256, 2, 2>(p, stream);
     case 6: return launch_tile<256, 64, 4, 1>(p, stream);
     case 7: return launch_tile<128, 32, 2, 1>(p, stream);
     default: return launch_tile<64, 64, 2, 2>(p, stream);

@@ -125,7 +125,7 @@ def test_gemm_handworked(golden):
 def test_gemm_config1():
     c = wl.config1()
     say(c.name)
-    run_gemm_case(c.a_codes, c.b_codes, c.za, c.zb, tiles=(-1, 0, 1, 2, 3, 4, 6, 7))
+    run_gemm_case(c.a_codes, c.b_codes, c.za, c.zb, tiles=(-1, 0, 1, 2, 3, 6, 7))
 
 
 @pytest.mark.parametrize("idx", range(27))
@@ -220,7 +220,7 @@ def test_gemm_is_deterministic_across_tiles():
     c = wl.gemm_case("det", 512, 384, 1152, seed=123)
     A, B = dev(o.pack(c.a_codes)), dev(o.pack(c.b_codes, transpose=True))
     outs = []
-    for tile in (0, 1, 2, 3, 4, 5, 6, 7, 0):
+    for tile in (0, 1, 2, 3, 6, 7, 0):
         q4.debug_force_tile(tile)
         outs.append(host(q4.q4_gemm(A, c.za, B, c.zb, c.M, c.N, c.K, q4.B_NK)).copy())
     q4.debug_force_tile(-1)
