@@ -1,0 +1,131 @@
+"""The pins must be able to fail: each plausible mistake is planted in a COPY of the oracle source
+(on the CPU), the copy is compiled, and a small battery of the pins (hand-worked values, tiny brute
+force, library routines) must reject it while accepting the real oracle."""
+import ctypes
+import itertools
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+from tests.conftest import read_golden
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = open(os.path.join(ROOT, "oracle", "q4_oracle.c")).read()
+
+MUTANTS = {
+    "nibble order swapped": ("return (row[j >> 1] >> (4 * (int)(j & 1))) & 15;",
+                             "return (row[j >> 1] >> (4 * (int)((j & 1) ^ 1))) & 15;"),
+    "sign of the weight zero point": ("s += (int64_t)(a - za) * (int64_t)(b - zb);", "s += (int64_t)(a - za) * (int64_t)(b + zb);"),
+    "activation zero point dropped": ("s += (int64_t)(a - za) * (int64_t)(b - zb);", "s += (int64_t)(a) * (int64_t)(b - zb);"),
+    "B indexed as its transpose": ("int b = b_layout == 0 ? q4o_code(B + k * ldb, n)", "int b = b_layout == 0 ? q4o_code(B + n * ldb, k)"),
+    "requant truncates toward zero": ("    if (p % d != 0 && p < 0) q -= 1;\n", ""),
+    "requant adds the zero point before scaling": ("int64_t p = (int64_t)acc[r * ld_acc + c] * (int64_t)mult;",
+                                                   "int64_t p = ((int64_t)acc[r * ld_acc + c] + zo) * (int64_t)mult;"),
+    "conv row offset uses the column tap": ("long ih = oh * sh + kh - ph;", "long ih = oh * sh + kw - ph;"),
+    "conv pads with code zero": ("                        int xv = zx;\n", "                        int xv = 0;\n"),
+    "conv depth order c slowest": ("int wv = q4o_code(w + oc * ldw, (kh * KW + kw) * C + c);", "int wv = q4o_code(w + oc * ldw, (c * KH + kh) * KW + kw);"),
+    "pool takes the minimum": ("if (v > best) best = v;", "if (v < best) best = v;"),
+    "quantizer rounds to nearest": ("int q = (int)__builtin_floorf(x[i] / s) + z;", "int q = (int)__builtin_floorf(x[i] / s + 0.5f) + z;"),
+}
+
+
+def _build(tmp_path, name, source):
+    c = tmp_path / f"{name}.c"
+    so = tmp_path / f"{name}.so"
+    c.write_text(source)
+    subprocess.check_call(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", str(so), str(c)])
+    lib = ctypes.CDLL(str(so))
+    L, I, P = ctypes.c_long, ctypes.c_int, ctypes.c_void_p
+    lib.q4o_pack.argtypes = [P, L, L, L, I, P, L]
+    lib.q4o_gemm.argtypes = [L, L, L, P, L, I, P, L, I, I, P, L]
+    lib.q4o_conv2d.argtypes = [L] * 11 + [P, I, P, I, P]
+    lib.q4o_requant.argtypes = [P, L, L, L, ctypes.c_int32, I, I, I, I, P, L]
+    lib.q4o_maxpool2x2.argtypes = [P, L, L, L, L, P]
+    lib.q4o_quantize_f32.argtypes = [P, L, P, P, P]
+    return lib
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _np_pack(codes):
+    """Storage convention restated in NumPy (element 2j low nibble, 2j+1 high nibble)."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    rows, cols = codes.shape
+    out = np.zeros((rows, (cols + 1) // 2), dtype=np.uint8)
+    for j in range(cols):
+        out[:, j // 2] |= (codes[:, j] & 15) << (4 * (j % 2))
+    return out
+
+
+def battery(lib) -> bool:
+    """True when the library passes a condensed set of the pins."""
+    g = read_golden("handworked.txt")
+    ok = True
+    # packed bytes of the hand-worked matrices
+    a = np.array(g["gemm_a"], dtype=np.uint8)
+    pa = np.zeros((2, 1), np.uint8)
+    lib.q4o_pack(_ptr(a), 2, 2, 2, 0, _ptr(pa), 1)
+    ok &= pa.tolist() == g["gemm_a_packed"]
+    # hand-worked product, both layouts of B
+    A = np.array(g["gemm_a_packed"], dtype=np.uint8)
+    for layout, key in ((0, "gemm_b_packed_kn"), (1, "gemm_b_packed_nk")):
+        B = np.array(g[key], dtype=np.uint8)
+        C = np.zeros((2, 2), np.int32)
+        lib.q4o_gemm(2, 2, 2, _ptr(A), 1, g["gemm_za"], _ptr(B), 1, g["gemm_zb"], layout, _ptr(C), 2)
+        ok &= C.tolist() == g["gemm_c"]
+    # non-square random product against NumPy int64
+    rng = np.random.default_rng(3)
+    a = rng.integers(0, 16, size=(3, 5), dtype=np.uint8)
+    b = rng.integers(0, 16, size=(5, 4), dtype=np.uint8)
+    C = np.zeros((3, 4), np.int32)
+    Ap, Bp = _np_pack(a), _np_pack(b)
+    lib.q4o_gemm(3, 4, 5, _ptr(Ap), Ap.shape[1], 6, _ptr(Bp), Bp.shape[1], 9, 0, _ptr(C), 4)
+    ok &= np.array_equal(C, (a.astype(np.int64) - 6) @ (b.astype(np.int64) - 9))
+    # hand-worked convolution with padding; a 2-channel, non-square one against the definition in NumPy
+    x = _np_pack(np.array(g["conv_x"], dtype=np.uint8).reshape(1, -1)).reshape(-1)
+    w = _np_pack(np.array(g["conv_w"], dtype=np.uint8).reshape(1, -1))
+    y = np.zeros((9, 1), np.int32)
+    lib.q4o_conv2d(1, 3, 3, 1, 3, 3, 1, 1, 1, 1, 1, _ptr(x), g["conv_zx"], _ptr(w), g["conv_zw"], _ptr(y))
+    ok &= y.reshape(3, 3).tolist() == g["conv_y"]
+    xc = rng.integers(0, 16, size=(1, 4, 5, 2), dtype=np.uint8)
+    wc = rng.integers(0, 16, size=(3, 2, 3, 2), dtype=np.uint8)          # OC x KH x KW x C
+    want = np.zeros((3 * 3, 3), np.int64)
+    for oh, ow, oc in itertools.product(range(3), range(3), range(3)):
+        patch = xc[0, oh:oh + 2, ow:ow + 3, :].astype(np.int64) - 5
+        want[oh * 3 + ow, oc] = (patch * (wc[oc].astype(np.int64) - 9)).sum()
+    y = np.zeros((9, 3), np.int32)
+    xp, wp = _np_pack(xc.reshape(1, -1)).reshape(-1), _np_pack(wc.reshape(3, -1))
+    lib.q4o_conv2d(1, 4, 5, 2, 2, 3, 1, 1, 0, 0, 3, _ptr(xp), 5, _ptr(wp), 9, _ptr(y))
+    ok &= np.array_equal(y, want)
+    # hand-worked re-quantization
+    for mult, acc, want_q in g["requant_a"] + g["requant_b"]:
+        out = np.zeros((1, 1), np.uint8)
+        lib.q4o_requant(_ptr(np.array([[acc]], np.int32)), 1, 1, 1, mult, 20, 8, 0, 15, _ptr(out), 1)
+        ok &= int(out[0, 0]) == want_q
+    # pooling and the float quantizer
+    px = _np_pack(np.array([[1, 9, 5, 2, 3, 4, 0, 15]], dtype=np.uint8)).reshape(-1)   # 1 x 2 x 2 x 2
+    py = np.zeros(1, np.uint8)
+    lib.q4o_maxpool2x2(_ptr(px), 1, 2, 2, 2, _ptr(py))
+    ok &= int(py[0]) == (5 | (15 << 4))
+    s, z, codes = g["quant_b"]
+    qx = np.array(g["quant_b_x"], dtype=np.float32)
+    qs, qz, qp = np.zeros(1, np.float32), np.zeros(1, np.int32), np.zeros(3, np.uint8)
+    lib.q4o_quantize_f32(_ptr(qx), 5, _ptr(qs), _ptr(qz), _ptr(qp))
+    got = [int(qp[i // 2] >> (4 * (i % 2))) & 15 for i in range(5)]
+    ok &= (float(qs[0]), int(qz[0]), got) == (s, z, codes)
+    return bool(ok)
+
+
+def test_the_real_oracle_passes_the_battery(tmp_path):
+    assert battery(_build(tmp_path, "real", SRC))
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_planted_mistake_is_caught(tmp_path, name):
+    old, new = MUTANTS[name]
+    assert SRC.count(old) == 1, f"mutation site for '{name}' not found exactly once"
+    assert not battery(_build(tmp_path, "mutant", SRC.replace(old, new))), f"'{name}' slipped through the pins"
