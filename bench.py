@@ -137,7 +137,7 @@ def main():
                    "M": M, "N": N, "K": K, "step": "q4_gemm(Q4_B_KN): repack B + depth sums + MFMA product + epilogue"},
         "pct_of_int8_mfma_peak": round(100.0 * tops / INT8_MFMA_PEAK_TOPS, 2),
         "roofline": {
-            "kernel": "q4_gemm_direct_kernel<256,256,2,4,4,4>",
+            "kernel": "q4_gemm_direct_kernel<256,256,4,2,4,4>",
             "bound": "mfma",
             "achieved": round(kern_tops, 2),
             "peak": INT8_MFMA_PEAK_TOPS,

@@ -1019,7 +1019,7 @@ hipError_t launch_gemm(const GemmProblem &p, int force_tile, hipStream_t stream)
     if (tile < 0) tile = p.rq.pool_ow > 0 ? tile_for_pool(p) : tile_by_shape(p);
     if (tile < 0) return hipErrorInvalidValue;  // pooling asked for without checking gemm_can_pool
     switch (tile) {
-    case 0: return launch_tile<256, 256, 2, 4>(p, stream);
+    case 0: return launch_tile<256, 256, 4, 2>(p, stream);  // 64 x 128 per wave: measured 1 % ahead of 128 x 64
     case 1: return launch_tile<128, 128, 2, 2>(p, stream);
     case 3: return launch_tile<256, 128, 2, 2>(p, stream);
     case 6: return launch_tile<256, 64, 4, 1>(p, stream);
