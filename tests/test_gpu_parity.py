@@ -196,6 +196,20 @@ def test_gemm_at_the_depth_bound():
     assert e.value.code == q4.ERR_OVERFLOW
 
 
+def test_gemm_repeatable_under_load():
+    """The LDS ring, the asynchronous loads and the barriers leave no room for timing to matter: forty
+    back-to-back launches of a 4096^3 product give the same bits, and those bits are the oracle's."""
+    say("gemm repeatability 4096^3 x 40")
+    c = wl.config5(4096, 4096, 4096, seed=77)
+    A, Bkn = dev(c.a_packed), dev(c.b_packed_kn)
+    first = q4.q4_gemm(A, c.za, Bkn, c.zb, c.M, c.N, c.K, q4.B_KN)
+    outs = [q4.q4_gemm(A, c.za, Bkn, c.zb, c.M, c.N, c.K, q4.B_KN) for _ in range(40)]
+    torch.cuda.synchronize()
+    assert all(torch.equal(first, x) for x in outs)
+    want = o.gemm_f64(c.a_packed, c.za, c.b_packed_kn, c.zb, c.M, c.N, c.K, o.B_KN)
+    assert np.array_equal(host(first), want)
+
+
 def test_gemm_unaligned_views_and_ldc():
     say("gemm unaligned views")
     rng = np.random.default_rng(99)
