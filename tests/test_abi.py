@@ -135,3 +135,26 @@ def test_binding_refuses_undersized_buffers():
         q4.q4_conv2d_im2col(q4.conv_desc(1, 64, 64, 32, 3, 3, (1, 1), (1, 1), 64), small, 0, small, 0)
     with pytest.raises(AssertionError):
         q4.q4_rowsum(small.reshape(32, 32), 100)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/q4.h must compile as C99 (no C++, no HIP or torch types) and link against the library."""
+    import subprocess
+    src = tmp_path / "use_q4.c"
+    src.write_text(
+        '#include "q4.h"\n'
+        '#include <stdio.h>\n'
+        'int main(void) {\n'
+        '    q4_conv_desc d = {1, 8, 8, 4, 3, 3, 1, 1, 1, 1, 4};\n'
+        '    printf("%d %d %zu %zu %s\\n", q4_version(), q4_max_depth(), q4_gemm_workspace_bytes(64, 32, 72, Q4_B_KN),\n'
+        '           q4_conv2d_workspace_bytes(&d), q4_strerror(Q4_ERR_OVERFLOW));\n'
+        '    return q4_gemm(0, 1, 1, 0, 0, 0, 0, 0, 0, Q4_B_NK, 0, 0, 0, 0, 0) == Q4_ERR_NULL ? 0 : 1;\n'
+        '}\n')
+    exe = tmp_path / "use_q4"
+    libdir = os.path.dirname(q4.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           str(src), "-o", str(exe), "-L", libdir, "-l:libq4.so", "-Wl,-rpath," + libdir,
+                           "-Wl,-rpath,/opt/rocm/lib"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert out.returncode == 0, out.stderr
+    assert out.stdout.split()[:2] == ["100", "9544371"]
